@@ -1,0 +1,491 @@
+// Host runtime behind the C ABI of include/smtm.h: context, device tables, argument checks,
+// launch order.  Every entry point validates its arguments before it touches the GPU and only
+// enqueues work on the caller's stream; the few calls that synchronise say so in the header.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "internal.h"
+
+using namespace smtm;
+
+struct smtm_ctx {
+    smtm_config cfg;
+    int device;
+    char err[512];
+
+    int n_pad;                                   // classes rounded up to kRowPad (fp16 operand rows)
+    int rows_pad;                                // max_batch rounded up to kRowPad
+    int Cp[SMTM_MAX_EXITS];                      // channels rounded up to kKPad
+    int Cp_max;
+
+    // global memory (Sec. 6): centres per exit point, update counts, tables
+    float* centres[SMTM_MAX_EXITS];              // [n, C_l] fp32 master
+    float* cinv[SMTM_MAX_EXITS];                 // [n] 1/|SC_j| (0 = degenerate)
+    _Float16* chat[SMTM_MAX_EXITS];              // [n_pad, Cp_l] unit fp16 copy, zero padded
+    uint32_t* mcount[SMTM_MAX_EXITS];            // [n]
+    uint32_t* FT;
+    uint32_t* TS;
+    // fast memory
+    int32_t* hot_ids;                            // [hot_max] policy order
+    uint8_t* in_hot;                             // [n]
+    int32_t* ids_stage;                          // [hot_max] staging for smtm_hot_set
+    // batch state
+    float* SA;                                   // [max_batch, n] by original frame id
+    float* sv[SMTM_MAX_EXITS];                   // [max_batch, C_l] by original frame id
+    float* vinv;                                 // [max_batch] by slot
+    _Float16* vhat;                              // [rows_pad, Cp_max] by slot
+    int32_t* live[2];                            // ping-pong live lists
+    int cur;
+    int32_t* next_slots;                         // old slot of each survivor
+    int32_t* decision;
+    int32_t* dlabel;
+    float* top_val;
+    int32_t* top_id;
+    int32_t* res_layer;
+    int32_t* res_label;
+    int32_t* res_tier;
+    Counts* counts;
+    // update scratch
+    uint32_t* cls_cnt;
+    int32_t* cls_last;
+    uint64_t* score;
+    int32_t* order;
+    // pinned staging for small host -> device copies
+    void* pinned;
+    size_t pinned_bytes;
+
+    // host-side bookkeeping
+    int batch;                                   // 0 = no batch begun
+    int stage_done[SMTM_MAX_EXITS];              // 0 none, 1 encoded, 2 looked up, 3 compacted
+    int enc_dtype[SMTM_MAX_EXITS];
+    int bound[SMTM_MAX_EXITS + 1];               // host upper bound of live rows entering exit point l (0-based)
+    std::vector<void*> allocs;
+};
+
+static char g_create_err[512] = "";
+
+static int32_t fail(smtm_ctx* ctx, int32_t code, const char* fmt, ...) {
+    char* dst = ctx ? ctx->err : g_create_err;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 512, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                   \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return fail(ctx, e_ == hipErrorOutOfMemory ? SMTM_ERR_NOMEM : SMTM_ERR_HIP,      \
+                        "%s failed: %s", #expr, hipGetErrorString(e_));                      \
+    } while (0)
+
+static int32_t check_launch(smtm_ctx* ctx, const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, SMTM_ERR_HIP, "%s: launch failed: %s", what, hipGetErrorString(e));
+    return SMTM_OK;
+}
+
+template <typename T>
+static hipError_t dev_alloc(smtm_ctx* ctx, T** p, size_t count) {
+    void* q = nullptr;
+    hipError_t e = hipMalloc(&q, count * sizeof(T) ? count * sizeof(T) : 1);
+    if (e == hipSuccess) { ctx->allocs.push_back(q); *p = static_cast<T*>(q); }
+    return e;
+}
+
+static int32_t validate_config(const smtm_config* c) {
+    if (!c) return fail(nullptr, SMTM_ERR_INVALID_ARG, "config is NULL");
+    if (c->n_classes < 2 || c->n_classes > SMTM_MAX_CLASSES)
+        return fail(nullptr, SMTM_ERR_INVALID_ARG, "n_classes %d outside 2..%d", c->n_classes, SMTM_MAX_CLASSES);
+    if (c->n_exits < 1 || c->n_exits > SMTM_MAX_EXITS)
+        return fail(nullptr, SMTM_ERR_INVALID_ARG, "n_exits %d outside 1..%d", c->n_exits, SMTM_MAX_EXITS);
+    for (int l = 0; l < c->n_exits; ++l)
+        if (c->dims[l] < 1 || c->dims[l] > 65536)
+            return fail(nullptr, SMTM_ERR_SHAPE, "dims[%d] = %d outside 1..65536", l, c->dims[l]);
+    if (c->max_batch < 1 || c->max_batch > SMTM_MAX_BATCH)
+        return fail(nullptr, SMTM_ERR_INVALID_ARG, "max_batch %d outside 1..%d", c->max_batch, SMTM_MAX_BATCH);
+    if (c->hot_min < 2 || c->hot_min > c->hot_init || c->hot_init > c->hot_max || c->hot_max > c->n_classes)
+        return fail(nullptr, SMTM_ERR_INVALID_ARG,
+                    "need 2 <= hot_min (%d) <= hot_init (%d) <= hot_max (%d) <= n_classes (%d)", c->hot_min,
+                    c->hot_init, c->hot_max, c->n_classes);
+    if (c->tiers != 1 && c->tiers != 2) return fail(nullptr, SMTM_ERR_INVALID_ARG, "tiers must be 1 or 2");
+    if (!(c->tau >= 0.f) || !(c->tau < __builtin_inff()))
+        return fail(nullptr, SMTM_ERR_INVALID_ARG, "tau must be finite and >= 0");
+    if (c->window < 1) return fail(nullptr, SMTM_ERR_INVALID_ARG, "window must be >= 1");
+    if (c->cl_num < 1 || c->cl_den < c->cl_num)
+        return fail(nullptr, SMTM_ERR_INVALID_ARG, "need 0 < cl_num <= cl_den");
+    if (c->init_count < 0) return fail(nullptr, SMTM_ERR_INVALID_ARG, "init_count must be >= 0");
+    if (c->score_path < SMTM_SCORE_AUTO || c->score_path > SMTM_SCORE_MFMA)
+        return fail(nullptr, SMTM_ERR_INVALID_ARG, "score_path must be one of SMTM_SCORE_*");
+    return SMTM_OK;
+}
+
+static int32_t check_ctx_exit(smtm_ctx* ctx, int32_t exit) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (exit < 1 || exit > ctx->cfg.n_exits)
+        return fail(ctx, SMTM_ERR_INVALID_ARG, "exit point %d outside 1..%d", exit, ctx->cfg.n_exits);
+    return SMTM_OK;
+}
+
+extern "C" {
+
+int32_t smtm_version(void) { return 100; }
+
+const char* smtm_last_error(const smtm_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
+
+int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
+    if (!out) return fail(nullptr, SMTM_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    int32_t rc = validate_config(cfg);
+    if (rc != SMTM_OK) return rc;
+    smtm_ctx* ctx = new (std::nothrow) smtm_ctx();
+    if (!ctx) return fail(nullptr, SMTM_ERR_NOMEM, "host allocation failed");
+    ctx->cfg = *cfg;
+    ctx->err[0] = 0;
+    const int n = cfg->n_classes, L = cfg->n_exits, B = cfg->max_batch;
+    ctx->n_pad = round_up(n, kRowPad);
+    ctx->rows_pad = round_up(B, kRowPad);
+    ctx->Cp_max = 0;
+    for (int l = 0; l < L; ++l) {
+        ctx->Cp[l] = round_up(cfg->dims[l], kKPad);
+        if (ctx->Cp[l] > ctx->Cp_max) ctx->Cp_max = ctx->Cp[l];
+    }
+#define CREATE_TRY(expr)                                                                         \
+    do {                                                                                         \
+        hipError_t e_ = (expr);                                                                  \
+        if (e_ != hipSuccess) {                                                                  \
+            rc = fail(nullptr, e_ == hipErrorOutOfMemory ? SMTM_ERR_NOMEM : SMTM_ERR_HIP,         \
+                      "%s failed: %s", #expr, hipGetErrorString(e_));                            \
+            smtm_destroy(ctx);                                                                   \
+            return rc;                                                                           \
+        }                                                                                        \
+    } while (0)
+    CREATE_TRY(hipGetDevice(&ctx->device));
+    for (int l = 0; l < L; ++l) {
+        const size_t C = cfg->dims[l];
+        CREATE_TRY(dev_alloc(ctx, &ctx->centres[l], (size_t)n * C));
+        CREATE_TRY(dev_alloc(ctx, &ctx->cinv[l], (size_t)n));
+        CREATE_TRY(dev_alloc(ctx, &ctx->chat[l], (size_t)ctx->n_pad * ctx->Cp[l]));
+        CREATE_TRY(dev_alloc(ctx, &ctx->mcount[l], (size_t)n));
+        CREATE_TRY(dev_alloc(ctx, &ctx->sv[l], (size_t)B * C));
+    }
+    CREATE_TRY(dev_alloc(ctx, &ctx->FT, (size_t)n));
+    CREATE_TRY(dev_alloc(ctx, &ctx->TS, (size_t)n));
+    CREATE_TRY(dev_alloc(ctx, &ctx->hot_ids, (size_t)cfg->hot_max));
+    CREATE_TRY(dev_alloc(ctx, &ctx->ids_stage, (size_t)cfg->hot_max));
+    CREATE_TRY(dev_alloc(ctx, &ctx->in_hot, (size_t)n));
+    CREATE_TRY(dev_alloc(ctx, &ctx->SA, (size_t)B * n));
+    CREATE_TRY(dev_alloc(ctx, &ctx->vinv, (size_t)B));
+    CREATE_TRY(dev_alloc(ctx, &ctx->vhat, (size_t)ctx->rows_pad * ctx->Cp_max));
+    CREATE_TRY(dev_alloc(ctx, &ctx->live[0], (size_t)B));
+    CREATE_TRY(dev_alloc(ctx, &ctx->live[1], (size_t)B));
+    CREATE_TRY(dev_alloc(ctx, &ctx->next_slots, (size_t)B));
+    CREATE_TRY(dev_alloc(ctx, &ctx->decision, (size_t)B));
+    CREATE_TRY(dev_alloc(ctx, &ctx->dlabel, (size_t)B));
+    CREATE_TRY(dev_alloc(ctx, &ctx->top_val, (size_t)B * 4));
+    CREATE_TRY(dev_alloc(ctx, &ctx->top_id, (size_t)B * 2));
+    CREATE_TRY(dev_alloc(ctx, &ctx->res_layer, (size_t)B));
+    CREATE_TRY(dev_alloc(ctx, &ctx->res_label, (size_t)B));
+    CREATE_TRY(dev_alloc(ctx, &ctx->res_tier, (size_t)B));
+    CREATE_TRY(dev_alloc(ctx, &ctx->counts, (size_t)1));
+    CREATE_TRY(dev_alloc(ctx, &ctx->cls_cnt, (size_t)n));
+    CREATE_TRY(dev_alloc(ctx, &ctx->cls_last, (size_t)n));
+    CREATE_TRY(dev_alloc(ctx, &ctx->score, (size_t)n));
+    CREATE_TRY(dev_alloc(ctx, &ctx->order, (size_t)n));
+    ctx->pinned_bytes = sizeof(int32_t) * (size_t)cfg->hot_max;
+    CREATE_TRY(hipHostMalloc(&ctx->pinned, ctx->pinned_bytes, hipHostMallocDefault));
+
+    // initial state on the null stream: zero centres / tables, fast memory = classes 0..hot_init-1
+    for (int l = 0; l < L; ++l) {
+        CREATE_TRY(hipMemset(ctx->centres[l], 0, sizeof(float) * (size_t)n * cfg->dims[l]));
+        CREATE_TRY(hipMemset(ctx->cinv[l], 0, sizeof(float) * (size_t)n));
+        CREATE_TRY(hipMemset(ctx->chat[l], 0, sizeof(_Float16) * (size_t)ctx->n_pad * ctx->Cp[l]));
+        CREATE_TRY(hipMemset(ctx->sv[l], 0, sizeof(float) * (size_t)B * cfg->dims[l]));
+        launch_fill_u32(ctx->mcount[l], (uint32_t)cfg->init_count, n, nullptr);
+    }
+    CREATE_TRY(hipMemset(ctx->FT, 0, sizeof(uint32_t) * (size_t)n));
+    CREATE_TRY(hipMemset(ctx->TS, 0, sizeof(uint32_t) * (size_t)n));
+    CREATE_TRY(hipMemset(ctx->counts, 0, sizeof(Counts)));
+    CREATE_TRY(hipMemset(ctx->vhat, 0, sizeof(_Float16) * (size_t)ctx->rows_pad * ctx->Cp_max));
+    CREATE_TRY(hipMemset(ctx->SA, 0, sizeof(float) * (size_t)B * n));
+    {
+        int32_t* ids = static_cast<int32_t*>(ctx->pinned);
+        for (int i = 0; i < cfg->hot_init; ++i) ids[i] = i;
+        CREATE_TRY(hipMemcpy(ctx->ids_stage, ids, sizeof(int32_t) * (size_t)cfg->hot_init, hipMemcpyHostToDevice));
+        launch_set_hot(ctx->ids_stage, cfg->hot_init, n, ctx->hot_ids, ctx->in_hot, ctx->counts, nullptr);
+    }
+    CREATE_TRY(hipGetLastError());
+    CREATE_TRY(hipDeviceSynchronize());
+#undef CREATE_TRY
+    ctx->batch = 0;
+    ctx->cur = 0;
+    *out = ctx;
+    return SMTM_OK;
+}
+
+int32_t smtm_destroy(smtm_ctx* ctx) {
+    if (!ctx) return SMTM_OK;
+    (void)hipDeviceSynchronize();
+    for (void* p : ctx->allocs) (void)hipFree(p);
+    if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    delete ctx;
+    return SMTM_OK;
+}
+
+int32_t smtm_memory_load(smtm_ctx* ctx, int32_t exit, const float* centres_host, void* stream) {
+    int32_t rc = check_ctx_exit(ctx, exit);
+    if (rc) return rc;
+    if (!centres_host) return fail(ctx, SMTM_ERR_INVALID_ARG, "centres_host is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int l = exit - 1, n = ctx->cfg.n_classes, C = ctx->cfg.dims[l];
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->centres[l], centres_host, sizeof(float) * (size_t)n * C, hipMemcpyHostToDevice, st));
+    launch_centre_prepare(ctx->centres[l], n, C, ctx->cinv[l], ctx->chat[l], ctx->Cp[l], 0, ctx->n_pad, st);
+    launch_fill_u32(ctx->mcount[l], (uint32_t)ctx->cfg.init_count, n, st);
+    return check_launch(ctx, "smtm_memory_load");
+}
+
+int32_t smtm_hot_set(smtm_ctx* ctx, const int32_t* ids, int32_t k, void* stream) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (!ids) return fail(ctx, SMTM_ERR_INVALID_ARG, "class_ids_host is NULL");
+    if (k < ctx->cfg.hot_min || k > ctx->cfg.hot_max)
+        return fail(ctx, SMTM_ERR_INVALID_ARG, "k = %d outside hot_min..hot_max (%d..%d)", k, ctx->cfg.hot_min, ctx->cfg.hot_max);
+    std::vector<uint8_t> seen((size_t)ctx->cfg.n_classes, 0);
+    for (int i = 0; i < k; ++i) {
+        if (ids[i] < 0 || ids[i] >= ctx->cfg.n_classes) return fail(ctx, SMTM_ERR_INVALID_ARG, "class id %d out of range", ids[i]);
+        if (seen[ids[i]]) return fail(ctx, SMTM_ERR_INVALID_ARG, "class id %d listed twice", ids[i]);
+        seen[ids[i]] = 1;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // the pinned staging buffer may still be in flight from an earlier call on this stream
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    memcpy(ctx->pinned, ids, sizeof(int32_t) * (size_t)k);
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->ids_stage, ctx->pinned, sizeof(int32_t) * (size_t)k, hipMemcpyHostToDevice, st));
+    launch_set_hot(ctx->ids_stage, k, ctx->cfg.n_classes, ctx->hot_ids, ctx->in_hot, ctx->counts, st);
+    return check_launch(ctx, "smtm_hot_set");
+}
+
+int32_t smtm_memory_export(smtm_ctx* ctx, int32_t exit, float* centres_host, uint32_t* counts_host, void* stream) {
+    int32_t rc = check_ctx_exit(ctx, exit);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int l = exit - 1, n = ctx->cfg.n_classes, C = ctx->cfg.dims[l];
+    if (centres_host) HIP_TRY(ctx, hipMemcpyAsync(centres_host, ctx->centres[l], sizeof(float) * (size_t)n * C, hipMemcpyDeviceToHost, st));
+    if (counts_host) HIP_TRY(ctx, hipMemcpyAsync(counts_host, ctx->mcount[l], sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    return SMTM_OK;
+}
+
+int32_t smtm_tables_export(smtm_ctx* ctx, uint32_t* ft, uint32_t* ts, int32_t* hot_ids, int32_t* k, void* stream) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int n = ctx->cfg.n_classes;
+    Counts c;
+    if (ft) HIP_TRY(ctx, hipMemcpyAsync(ft, ctx->FT, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToHost, st));
+    if (ts) HIP_TRY(ctx, hipMemcpyAsync(ts, ctx->TS, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToHost, st));
+    if (hot_ids) HIP_TRY(ctx, hipMemcpyAsync(hot_ids, ctx->hot_ids, sizeof(int32_t) * (size_t)ctx->cfg.hot_max, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipMemcpyAsync(&c, ctx->counts, sizeof(Counts), hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    if (k) *k = c.hot_k;
+    return SMTM_OK;
+}
+
+int32_t smtm_tables_import(smtm_ctx* ctx, const uint32_t* ft, const uint32_t* ts, void* stream) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int n = ctx->cfg.n_classes;
+    if (ft) HIP_TRY(ctx, hipMemcpyAsync(ctx->FT, ft, sizeof(uint32_t) * (size_t)n, hipMemcpyHostToDevice, st));
+    if (ts) HIP_TRY(ctx, hipMemcpyAsync(ctx->TS, ts, sizeof(uint32_t) * (size_t)n, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    return SMTM_OK;
+}
+
+int32_t smtm_set_tau(smtm_ctx* ctx, float tau) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (!(tau >= 0.f) || !(tau < __builtin_inff())) return fail(ctx, SMTM_ERR_INVALID_ARG, "tau must be finite and >= 0");
+    ctx->cfg.tau = tau;
+    return SMTM_OK;
+}
+
+int32_t smtm_begin_batch(smtm_ctx* ctx, int32_t batch, void* stream) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (batch < 1 || batch > ctx->cfg.max_batch)
+        return fail(ctx, SMTM_ERR_SHAPE, "batch %d outside 1..max_batch (%d)", batch, ctx->cfg.max_batch);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ctx->cur = 0;
+    launch_begin_batch(ctx->SA, ctx->cfg.n_classes, batch, ctx->live[0], ctx->res_layer, ctx->res_label,
+                       ctx->res_tier, ctx->counts, st);
+    int32_t rc = check_launch(ctx, "smtm_begin_batch");
+    if (rc) return rc;
+    ctx->batch = batch;
+    for (int l = 0; l < SMTM_MAX_EXITS; ++l) ctx->stage_done[l] = 0;
+    for (int l = 0; l <= SMTM_MAX_EXITS; ++l) ctx->bound[l] = batch;
+    return SMTM_OK;
+}
+
+static int32_t check_encode_args(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W) {
+    int32_t rc = check_ctx_exit(ctx, exit);
+    if (rc) return rc;
+    if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");
+    if (!fmap) return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap is NULL");
+    if ((reinterpret_cast<uintptr_t>(fmap) & 15u) != 0) return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap must be 16-byte aligned");
+    if (dtype != SMTM_F16 && dtype != SMTM_F32) return fail(ctx, SMTM_ERR_UNSUPPORTED, "dtype %d is neither SMTM_F16 nor SMTM_F32", dtype);
+    if (H < 1 || W < 1 || (int64_t)H * W > (1 << 24)) return fail(ctx, SMTM_ERR_SHAPE, "H x W = %d x %d not supported", H, W);
+    return SMTM_OK;
+}
+
+int32_t smtm_encode(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
+                    const int32_t* row_ids, float* sv_out, void* stream) {
+    int32_t rc = check_encode_args(ctx, exit, fmap, dtype, H, W);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int l = exit - 1;
+    launch_encode(fmap, dtype, ctx->cfg.dims[l], H * W, row_ids, ctx->live[ctx->cur], ctx->counts, ctx->batch,
+                  ctx->sv[l], sv_out, st);
+    rc = check_launch(ctx, "smtm_encode");
+    if (rc) return rc;
+    ctx->stage_done[l] = 1;
+    ctx->enc_dtype[l] = dtype;
+    return SMTM_OK;
+}
+
+int32_t smtm_lookup(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id, float* sims_out, void* stream) {
+    int32_t rc = check_ctx_exit(ctx, exit);
+    if (rc) return rc;
+    const int l = exit - 1;
+    if (ctx->batch == 0 || ctx->stage_done[l] != 1)
+        return fail(ctx, SMTM_ERR_STATE, "smtm_lookup(%d) needs smtm_encode(%d) first, once per batch", exit, exit);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int n = ctx->cfg.n_classes, C = ctx->cfg.dims[l], B = ctx->batch;
+    const int32_t* live = ctx->live[ctx->cur];
+    int path = ctx->cfg.score_path;
+    if (path == SMTM_SCORE_AUTO) path = ctx->enc_dtype[l] == SMTM_F16 ? SMTM_SCORE_MFMA : SMTM_SCORE_FP32;
+    const float weight = ldexpf(1.0f, exit - 1);
+    if (path == SMTM_SCORE_MFMA) {
+        launch_rownorm(ctx->sv[l], live, ctx->counts, B, C, ctx->vinv, ctx->vhat, ctx->Cp[l], st);
+        launch_score_mfma(ctx->vhat, ctx->chat[l], ctx->Cp[l], live, ctx->counts, B, n, weight, ctx->SA, sims_out, st);
+    } else {
+        launch_rownorm(ctx->sv[l], live, ctx->counts, B, C, ctx->vinv, nullptr, 0, st);
+        launch_score_fp32(ctx->sv[l], live, ctx->counts, B, ctx->vinv, ctx->centres[l], ctx->cinv[l], n, C, weight,
+                          ctx->SA, sims_out, st);
+    }
+    launch_top2_decide(ctx->SA, live, ctx->counts, B, n, ctx->in_hot, ctx->cfg.tiers, ctx->cfg.tau, ctx->decision,
+                       ctx->dlabel, ctx->top_val, ctx->top_id, top_val, top_id, st);
+    rc = check_launch(ctx, "smtm_lookup");
+    if (rc) return rc;
+    ctx->stage_done[l] = 2;
+    return SMTM_OK;
+}
+
+int32_t smtm_exit_compact(smtm_ctx* ctx, int32_t exit, int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
+                          int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev, const void* fmap_in,
+                          const int32_t* row_ids, void* fmap_out, int64_t row_bytes, void* stream) {
+    int32_t rc = check_ctx_exit(ctx, exit);
+    if (rc) return rc;
+    const int l = exit - 1;
+    if (ctx->batch == 0 || ctx->stage_done[l] != 2)
+        return fail(ctx, SMTM_ERR_STATE, "smtm_exit_compact(%d) needs smtm_lookup(%d) first, once per batch", exit, exit);
+    if ((fmap_in != nullptr) != (fmap_out != nullptr))
+        return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_in and fmap_out must be given together");
+    if (fmap_out) {
+        if (row_bytes < 2 || (row_bytes & 1)) return fail(ctx, SMTM_ERR_SHAPE, "row_bytes %lld must be even and >= 2", (long long)row_bytes);
+        if (((reinterpret_cast<uintptr_t>(fmap_in) | reinterpret_cast<uintptr_t>(fmap_out)) & 15u) != 0)
+            return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_in and fmap_out must be 16-byte aligned");
+        if (fmap_in == fmap_out) return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_out must not overlap fmap_in");
+    }
+    const int32_t* cur = ctx->live[ctx->cur];
+    int32_t* nxt = ctx->live[ctx->cur ^ 1];
+    if (live_ids == cur || live_ids == nxt || row_ids == nxt)
+        return fail(ctx, SMTM_ERR_INVALID_ARG, "live_ids / row_ids alias the context's next live list");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    launch_compact(ctx->decision, ctx->dlabel, cur, nxt, ctx->next_slots, ctx->counts, exit, exit_ids, exit_labels,
+                   exit_tier, n_exit_dev, live_ids, n_live_dev, ctx->res_layer, ctx->res_label, ctx->res_tier, st);
+    if (fmap_out)
+        launch_gather_rows(fmap_in, row_ids, ctx->next_slots, ctx->counts, ctx->batch, fmap_out, row_bytes, st);
+    rc = check_launch(ctx, "smtm_exit_compact");
+    if (rc) return rc;
+    ctx->cur ^= 1;
+    ctx->stage_done[l] = 3;
+    return SMTM_OK;
+}
+
+int32_t smtm_stage(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
+                   const int32_t* row_ids, int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
+                   int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev, void* fmap_out, void* stream) {
+    int32_t rc = check_encode_args(ctx, exit, fmap, dtype, H, W);
+    if (rc) return rc;
+    const int l = exit - 1;
+    if (fmap_out) {
+        if ((reinterpret_cast<uintptr_t>(fmap_out) & 15u) != 0) return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_out must be 16-byte aligned");
+        if (fmap_out == fmap) return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_out must not overlap fmap");
+    }
+    const int32_t* nxt = ctx->live[ctx->cur ^ 1];
+    if (live_ids == ctx->live[ctx->cur] || live_ids == nxt || row_ids == nxt)
+        return fail(ctx, SMTM_ERR_INVALID_ARG, "live_ids / row_ids alias the context's next live list");
+    rc = smtm_encode(ctx, exit, fmap, dtype, H, W, row_ids, nullptr, stream);
+    if (rc) return rc;
+    rc = smtm_lookup(ctx, exit, nullptr, nullptr, nullptr, stream);
+    if (rc) return rc;
+    const int64_t row_bytes = (int64_t)ctx->cfg.dims[l] * H * W * (dtype == SMTM_F16 ? 2 : 4);
+    return smtm_exit_compact(ctx, exit, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids, n_live_dev,
+                             fmap_out ? fmap : nullptr, row_ids, fmap_out, row_bytes, stream);
+}
+
+const int32_t* smtm_live_ids(const smtm_ctx* ctx) { return ctx ? ctx->live[ctx->cur] : nullptr; }
+
+int32_t smtm_batch_results(smtm_ctx* ctx, int32_t* exit_layer, int32_t* label, int32_t* tier, void* stream) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (exit_layer) launch_copy_i32(ctx->res_layer, exit_layer, ctx->batch, st);
+    if (label) launch_copy_i32(ctx->res_label, label, ctx->batch, st);
+    if (tier) launch_copy_i32(ctx->res_tier, tier, ctx->batch, st);
+    return check_launch(ctx, "smtm_batch_results");
+}
+
+int32_t smtm_read_counts(smtm_ctx* ctx, int32_t* n_live_host, int32_t* n_exit_host, void* stream) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Counts c;
+    HIP_TRY(ctx, hipMemcpyAsync(&c, ctx->counts, sizeof(Counts), hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    if (n_live_host) *n_live_host = c.n_live;
+    if (n_exit_host) *n_exit_host = c.n_exit;
+    return SMTM_OK;
+}
+
+int32_t smtm_read_stats(smtm_ctx* ctx, int32_t* stats_host, void* stream) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (!stats_host) return fail(ctx, SMTM_ERR_INVALID_ARG, "stats_host is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Counts c;
+    HIP_TRY(ctx, hipMemcpyAsync(&c, ctx->counts, sizeof(Counts), hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    for (int l = 0; l < ctx->cfg.n_exits; ++l)
+        for (int i = 0; i < 4; ++i) stats_host[l * 4 + i] = c.stats[l][i];
+    return SMTM_OK;
+}
+
+int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* stop_layer, int32_t batch, void* stream) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (!label || !stop_layer) return fail(ctx, SMTM_ERR_INVALID_ARG, "label / stop_layer is NULL");
+    if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");
+    if (batch != ctx->batch) return fail(ctx, SMTM_ERR_SHAPE, "batch %d differs from the batch begun (%d)", batch, ctx->batch);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const smtm_config& c = ctx->cfg;
+    const int n = c.n_classes;
+    launch_tables_update(label, batch, n, ctx->FT, ctx->TS, ctx->cls_cnt, ctx->cls_last, st);
+    for (int l = 0; l < c.n_exits; ++l)
+        launch_centres_update(ctx->centres[l], ctx->mcount[l], ctx->cinv[l], ctx->chat[l], ctx->Cp[l], ctx->sv[l],
+                              c.dims[l], n, l, label, stop_layer, batch, ctx->cls_cnt, st);
+    launch_policy(ctx->FT, ctx->TS, n, (uint32_t)c.window, (uint32_t)c.cl_num, (uint32_t)c.cl_den, c.hot_min,
+                  c.hot_max, ctx->score, ctx->order, ctx->hot_ids, ctx->in_hot, ctx->counts, st);
+    return check_launch(ctx, "smtm_cache_update");
+}
+
+}  // extern "C"

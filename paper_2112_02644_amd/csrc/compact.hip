@@ -1,0 +1,199 @@
+// Exit and compact: frames released at an exit point leave the batch, the others continue
+// (arXiv 2112.02644, Sec. 1 "skips the rest layers", Sec. 5 last paragraph).  For a batch this
+// is a stable partition of the live list: wavefront ballot + popcount prefix inside a
+// wavefront, an LDS scan across the wavefronts of one block, running bases across chunks.
+// No atomics decide positions, so the lists come out in ascending frame id on every run.
+#include "internal.h"
+
+namespace smtm {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void k_begin_batch(float* __restrict__ SA, int n, int batch,
+                                                     int32_t* __restrict__ live,
+                                                     int32_t* __restrict__ res_layer,
+                                                     int32_t* __restrict__ res_label,
+                                                     int32_t* __restrict__ res_tier,
+                                                     Counts* __restrict__ counts) {
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t total = (int64_t)batch * n;
+    for (int64_t i = tid; i < total; i += stride) SA[i] = 0.f;
+    for (int64_t i = tid; i < batch; i += stride) {
+        live[i] = (int32_t)i;
+        res_layer[i] = 0; res_label[i] = -1; res_tier[i] = 0;
+    }
+    if (tid == 0) { counts->n_live = batch; counts->n_exit = 0; }
+    if (tid < SMTM_MAX_EXITS * 4) counts->stats[tid >> 2][tid & 3] = 0;
+}
+
+void launch_begin_batch(float* SA, int n, int batch, int32_t* live, int32_t* res_layer,
+                        int32_t* res_label, int32_t* res_tier, Counts* counts, hipStream_t st) {
+    int64_t total = (int64_t)batch * n;
+    int grid = (int)((total + 1023) / 1024);
+    if (grid > 1024) grid = 1024;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(k_begin_batch, dim3(grid), dim3(256), 0, st, SA, n, batch, live, res_layer,
+                       res_label, res_tier, counts);
+}
+
+// One block of 1024 threads (16 wavefronts) walks the live list in chunks of 1024 slots.
+__global__ __launch_bounds__(1024) void k_compact(
+    const int32_t* __restrict__ decision, const int32_t* __restrict__ label,
+    const int32_t* __restrict__ frame_ids, int32_t* __restrict__ next_ids,
+    int32_t* __restrict__ next_slots, Counts* __restrict__ counts, int exit_index,
+    int32_t* __restrict__ exit_ids, int32_t* __restrict__ exit_labels,
+    int32_t* __restrict__ exit_tier, int32_t* __restrict__ n_exit_dev,
+    int32_t* __restrict__ live_ids_user, int32_t* __restrict__ n_live_dev,
+    int32_t* __restrict__ res_layer, int32_t* __restrict__ res_label, int32_t* __restrict__ res_tier) {
+    __shared__ int w_exit[16], w_t1[16];
+    __shared__ int base_exit, base_t1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_live = counts->n_live;
+    if (tid == 0) { base_exit = 0; base_t1 = 0; }
+    __syncthreads();
+    for (int c0 = 0; c0 < n_live; c0 += 1024) {          // uniform over the block
+        const int slot = c0 + tid;
+        const bool valid = slot < n_live;
+        const int d = valid ? decision[slot] : 0;
+        const bool ex = valid && d != 0;
+        const unsigned long long m_ex = __ballot(ex);
+        const unsigned long long m_t1 = __ballot(valid && d == 1);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        const int pre_ex = __popcll(m_ex & below);
+        if (lane == 0) { w_exit[wave] = __popcll(m_ex); w_t1[wave] = __popcll(m_t1); }
+        __syncthreads();
+        int off_ex = 0, tot_ex = 0, tot_t1 = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) off_ex += w_exit[w];
+            tot_ex += w_exit[w]; tot_t1 += w_t1[w];
+        }
+        const int be = base_exit;
+        if (valid) {
+            const int frame = frame_ids[slot];
+            if (ex) {
+                const int pos = be + off_ex + pre_ex;
+                const int lab = label[slot];
+                if (exit_ids) exit_ids[pos] = frame;
+                if (exit_labels) exit_labels[pos] = lab;
+                if (exit_tier) exit_tier[pos] = d;
+                res_layer[frame] = exit_index; res_label[frame] = lab; res_tier[frame] = d;
+            } else {
+                // survivors before this slot = slots before it minus exits before it
+                const int pos = slot - (be + off_ex + pre_ex);
+                next_ids[pos] = frame;
+                next_slots[pos] = slot;
+                if (live_ids_user) live_ids_user[pos] = frame;
+            }
+        }
+        __syncthreads();
+        if (tid == 0) { base_exit = be + tot_ex; base_t1 += tot_t1; }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const int ne = base_exit, nl = n_live - base_exit;
+        counts->stats[exit_index - 1][0] = n_live;
+        counts->stats[exit_index - 1][1] = base_t1;
+        counts->stats[exit_index - 1][2] = ne - base_t1;
+        counts->n_exit = ne;
+        counts->n_live = nl;
+        if (n_exit_dev) *n_exit_dev = ne;
+        if (n_live_dev) *n_live_dev = nl;
+    }
+}
+
+void launch_compact(const int32_t* decision, const int32_t* label, const int32_t* frame_ids,
+                    int32_t* next_ids, int32_t* next_slots, Counts* counts, int exit_index,
+                    int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier, int32_t* n_exit_dev,
+                    int32_t* live_ids_user, int32_t* n_live_dev, int32_t* res_layer,
+                    int32_t* res_label, int32_t* res_tier, hipStream_t st) {
+    hipLaunchKernelGGL(k_compact, dim3(1), dim3(1024), 0, st, decision, label, frame_ids, next_ids,
+                       next_slots, counts, exit_index, exit_ids, exit_labels, exit_tier, n_exit_dev,
+                       live_ids_user, n_live_dev, res_layer, res_label, res_tier);
+}
+
+// Gather of the survivors' feature-map rows: new slot s copies the row that old slot
+// next_slots[s] read.  VB bytes per lane per access.
+template <typename V>
+__global__ __launch_bounds__(256) void k_gather_rows(const char* __restrict__ src,
+                                                     const int32_t* __restrict__ row_ids,
+                                                     const int32_t* __restrict__ next_slots,
+                                                     const Counts* __restrict__ counts, int max_rows,
+                                                     char* __restrict__ dst, int64_t row_bytes) {
+    int n_live = counts->n_live;                          // survivors (k_compact has run)
+    if (n_live > max_rows) n_live = max_rows;
+    const int64_t per_row = row_bytes / (int64_t)sizeof(V);
+    for (int s = blockIdx.y; s < n_live; s += gridDim.y) {
+        const int old_slot = next_slots[s];
+        const int64_t row = row_ids ? row_ids[old_slot] : old_slot;
+        const V* from = reinterpret_cast<const V*>(src + row * row_bytes);
+        V* to = reinterpret_cast<V*>(dst + (int64_t)s * row_bytes);
+        for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < per_row;
+             q += (int64_t)gridDim.x * blockDim.x)
+            __builtin_nontemporal_store(__builtin_nontemporal_load(from + q), to + q);
+    }
+}
+
+void launch_gather_rows(const void* src, const int32_t* row_ids, const int32_t* next_slots,
+                        const Counts* counts, int max_rows, void* dst, int64_t row_bytes,
+                        hipStream_t st) {
+    const int64_t unit = row_bytes % 16 == 0 ? 16 : (row_bytes % 4 == 0 ? 4 : 2);
+    int64_t gx = row_bytes / unit / (256 * 8);
+    if (gx < 1) gx = 1;
+    if (gx > 64) gx = 64;
+    int64_t gy = 4096 / gx;
+    if (gy > max_rows) gy = max_rows;
+    if (gy < 1) gy = 1;
+    const dim3 grid((unsigned)gx, (unsigned)gy);
+    const char* s = static_cast<const char*>(src);
+    char* d = static_cast<char*>(dst);
+    if (row_bytes % 16 == 0)
+        hipLaunchKernelGGL((k_gather_rows<u32x4>), grid, dim3(256), 0, st, s, row_ids, next_slots, counts, max_rows, d, row_bytes);
+    else if (row_bytes % 4 == 0)
+        hipLaunchKernelGGL((k_gather_rows<uint32_t>), grid, dim3(256), 0, st, s, row_ids, next_slots, counts, max_rows, d, row_bytes);
+    else
+        hipLaunchKernelGGL((k_gather_rows<uint16_t>), grid, dim3(256), 0, st, s, row_ids, next_slots, counts, max_rows, d, row_bytes);
+}
+
+__global__ void k_copy_i32(const int32_t* __restrict__ src, int32_t* __restrict__ dst, int count) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+void launch_copy_i32(const int32_t* src, int32_t* dst, int count, hipStream_t st) {
+    if (count <= 0) return;
+    int grid = (count + 255) / 256;
+    if (grid > 256) grid = 256;
+    hipLaunchKernelGGL(k_copy_i32, dim3(grid), dim3(256), 0, st, src, dst, count);
+}
+
+__global__ void k_fill_u32(uint32_t* __restrict__ dst, uint32_t value, int count) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += gridDim.x * blockDim.x) dst[i] = value;
+}
+
+void launch_fill_u32(uint32_t* dst, uint32_t value, int count, hipStream_t st) {
+    if (count <= 0) return;
+    int grid = (count + 255) / 256;
+    if (grid > 256) grid = 256;
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid), dim3(256), 0, st, dst, value, count);
+}
+
+// Fast-memory set from a list of class ids (already validated on the host: distinct, in range).
+__global__ void k_set_hot(const int32_t* __restrict__ ids, int k, int n, int32_t* __restrict__ hot_ids,
+                          uint8_t* __restrict__ in_hot, Counts* __restrict__ counts) {
+    // single block
+    for (int i = threadIdx.x; i < n; i += blockDim.x) in_hot[i] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < k; i += blockDim.x) {
+        const int j = ids[i];
+        hot_ids[i] = j;
+        in_hot[j] = 1;
+    }
+    if (threadIdx.x == 0) counts->hot_k = k;
+}
+
+void launch_set_hot(const int32_t* ids, int k, int n, int32_t* hot_ids, uint8_t* in_hot, Counts* counts,
+                    hipStream_t st) {
+    hipLaunchKernelGGL(k_set_hot, dim3(1), dim3(1024), 0, st, ids, k, n, hot_ids, in_hot, counts);
+}
+
+}  // namespace smtm

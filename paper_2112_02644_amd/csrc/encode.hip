@@ -1,0 +1,247 @@
+// Encode: semantic vector = global average pooling of each channel's H x W map
+// (arXiv 2112.02644, Sec. 4.1).  The feature map is read exactly once, in place, with the
+// widest loads its shape allows; sums are kept in fp32.
+//
+// Two streaming paths:
+//   direct  a group of g lanes (g = 1..64, a power of two) owns one channel and walks it with
+//           VB-byte loads, up to UNR loads in flight per lane; 64/g channels per wavefront.
+//           Used when a channel's H*W*elem bytes are a multiple of VB.
+//   lds     for short, oddly sized channels (e.g. 7x7 fp16 = 98 B): a wavefront streams 64
+//           consecutive channels (one contiguous piece of the frame) with 16-byte loads into
+//           its own LDS region, then lane c adds up channel c from LDS.
+// Work is taken in a grid-stride loop bounded by the live count read on the device.
+#include "internal.h"
+
+namespace smtm {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float sum_halves(uint32_t w) {
+    half2_t h = __builtin_bit_cast(half2_t, w);
+    return (float)h.x + (float)h.y;
+}
+
+template <typename T, int VB> struct Chunk;
+
+template <> struct Chunk<_Float16, 16> {
+    typedef u32x4 V;
+    static __device__ __forceinline__ float sum(V v) {
+        return (sum_halves(v.x) + sum_halves(v.y)) + (sum_halves(v.z) + sum_halves(v.w));
+    }
+};
+template <> struct Chunk<_Float16, 8> {
+    typedef u32x2 V;
+    static __device__ __forceinline__ float sum(V v) { return sum_halves(v.x) + sum_halves(v.y); }
+};
+template <> struct Chunk<_Float16, 4> {
+    typedef uint32_t V;
+    static __device__ __forceinline__ float sum(V v) { return sum_halves(v); }
+};
+template <> struct Chunk<_Float16, 2> {
+    typedef _Float16 V;
+    static __device__ __forceinline__ float sum(V v) { return (float)v; }
+};
+template <> struct Chunk<float, 16> {
+    typedef f32x4 V;
+    static __device__ __forceinline__ float sum(V v) { return (v.x + v.y) + (v.z + v.w); }
+};
+template <> struct Chunk<float, 8> {
+    typedef f32x2 V;
+    static __device__ __forceinline__ float sum(V v) { return v.x + v.y; }
+};
+template <> struct Chunk<float, 4> {
+    typedef float V;
+    static __device__ __forceinline__ float sum(V v) { return v; }
+};
+
+template <typename T, int VB, int UNR>
+__global__ __launch_bounds__(256) void k_encode_direct(
+    const T* __restrict__ F, const int32_t* __restrict__ row_ids,
+    const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows,
+    float* __restrict__ sv, float* __restrict__ sv_out, int C, int HW, int g_log2) {
+    typedef typename Chunk<T, VB>::V V;
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int n_waves = gridDim.x * (blockDim.x >> 6);
+    const int g = 1 << g_log2;
+    const int sub = lane & (g - 1);
+    const int grp = lane >> g_log2;
+    const int cpw = 64 >> g_log2;                       // channels per wavefront task
+    const int tpf = (C + cpw - 1) / cpw;                // tasks per frame
+    const int nv = (int)((int64_t)HW * sizeof(T) / VB); // chunks per channel
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    const int64_t total = (int64_t)n_live * tpf;
+    const float inv_hw = 1.0f / (float)HW;
+    (void)inv_hw;
+
+    for (int64_t t = wave; t < total; t += n_waves) {
+        const int slot = (int)(t / tpf);
+        const int c = (int)(t - (int64_t)slot * tpf) * cpw + grp;
+        const int64_t row = row_ids ? row_ids[slot] : slot;
+        float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+        if (c < C) {
+            const char* p = reinterpret_cast<const char*>(F) + ((row * C + c) * (int64_t)HW) * sizeof(T);
+            for (int base = 0; base < nv; base += UNR << g_log2) {
+                V v[UNR];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    const int idx = base + (u << g_log2) + sub;
+                    if (idx < nv)
+                        v[u] = __builtin_nontemporal_load(reinterpret_cast<const V*>(p + (int64_t)idx * VB));
+                    else
+                        v[u] = V{};
+                }
+#pragma unroll
+                for (int u = 0; u < UNR; u += 4) {
+                    acc0 += Chunk<T, VB>::sum(v[u]);
+                    if (u + 1 < UNR) acc1 += Chunk<T, VB>::sum(v[u + 1]);
+                    if (u + 2 < UNR) acc2 += Chunk<T, VB>::sum(v[u + 2]);
+                    if (u + 3 < UNR) acc3 += Chunk<T, VB>::sum(v[u + 3]);
+                }
+            }
+        }
+        float acc = (acc0 + acc1) + (acc2 + acc3);
+        for (int off = g >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+        if (sub == 0 && c < C) {
+            const float m = acc / (float)HW;
+            sv[(int64_t)frame_ids[slot] * C + c] = m;
+            if (sv_out) sv_out[(int64_t)slot * C + c] = m;
+        }
+    }
+}
+
+// lds path.  Dynamic LDS: 4 wavefronts x (64 * HW * sizeof(T)) bytes, each a multiple of 16.
+template <typename T, int UNR>
+__global__ __launch_bounds__(256) void k_encode_lds(
+    const T* __restrict__ F, const int32_t* __restrict__ row_ids,
+    const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows,
+    float* __restrict__ sv, float* __restrict__ sv_out, int C, int HW) {
+    extern __shared__ u32x4 lds16[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int tile_bytes = 64 * HW * (int)sizeof(T);
+    u32x4* my16 = lds16 + wave * (tile_bytes >> 4);
+    const T* myT = reinterpret_cast<const T*>(my16);
+    const int gpf = (C + 63) >> 6;                       // 64-channel groups per frame
+    const int bpf = (gpf + 3) >> 2;                      // block tasks per frame
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    const int64_t total = (int64_t)n_live * bpf;
+
+    for (int64_t t = blockIdx.x; t < total; t += gridDim.x) {    // uniform over the block
+        const int slot = (int)(t / bpf);
+        const int cg = (int)(t - (int64_t)slot * bpf) * 4 + wave;
+        const bool active = cg < gpf;
+        int nch = 0;
+        if (active) {
+            nch = C - cg * 64;
+            if (nch > 64) nch = 64;
+            const int64_t row = row_ids ? row_ids[slot] : slot;
+            const T* p = F + (row * C + (int64_t)cg * 64) * HW;
+            const int bytes = nch * HW * (int)sizeof(T);
+            const int nfull = bytes >> 4;
+            const u32x4* p16 = reinterpret_cast<const u32x4*>(p);
+            for (int base = 0; base < nfull; base += 64 * UNR) {
+                u32x4 v[UNR];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    const int idx = base + u * 64 + lane;
+                    if (idx < nfull) v[u] = __builtin_nontemporal_load(p16 + idx);
+                }
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    const int idx = base + u * 64 + lane;
+                    if (idx < nfull) my16[idx] = v[u];
+                }
+            }
+            const int done = (nfull << 4) / (int)sizeof(T);         // elements covered by whole chunks
+            const int rem = nch * HW - done;                        // < 16 / sizeof(T)
+            if (lane < rem) const_cast<T*>(myT)[done + lane] = p[done + lane];
+        }
+        __syncthreads();
+        if (active && lane < nch) {
+            const T* q = myT + lane * HW;
+            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+            int i = 0;
+            for (; i + 4 <= HW; i += 4) {
+                a0 += (float)q[i]; a1 += (float)q[i + 1]; a2 += (float)q[i + 2]; a3 += (float)q[i + 3];
+            }
+            for (; i < HW; ++i) a0 += (float)q[i];
+            const float m = ((a0 + a1) + (a2 + a3)) / (float)HW;
+            const int c = cg * 64 + lane;
+            sv[(int64_t)frame_ids[slot] * C + c] = m;
+            if (sv_out) sv_out[(int64_t)slot * C + c] = m;
+        }
+        __syncthreads();
+    }
+}
+
+static int encode_grid(int64_t tasks_upper, int waves_per_block) {
+    // enough resident wavefronts to cover HBM latency on 256 CUs, and no more blocks than tasks
+    int64_t blocks = (tasks_upper + waves_per_block - 1) / waves_per_block;
+    const int64_t cap = 256 * 8;
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
+template <typename T, int VB>
+static void launch_direct(const void* fmap, int C, int HW, const int32_t* row_ids,
+                          const int32_t* frame_ids, const Counts* counts, int max_rows, float* sv,
+                          float* sv_out, hipStream_t st) {
+    constexpr int UNR = 8;
+    const int nv = (int)((int64_t)HW * sizeof(T) / VB);
+    int g_log2 = 0;
+    while (g_log2 < 6 && (nv + (1 << g_log2) - 1) / (1 << g_log2) > UNR) ++g_log2;
+    const int cpw = 64 >> g_log2;
+    const int64_t tasks = (int64_t)max_rows * ((C + cpw - 1) / cpw);
+    const int grid = encode_grid(tasks, 4);
+    hipLaunchKernelGGL((k_encode_direct<T, VB, UNR>), dim3(grid), dim3(256), 0, st,
+                       static_cast<const T*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out,
+                       C, HW, g_log2);
+}
+
+const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
+                          const int32_t* frame_ids, const Counts* counts, int max_rows,
+                          float* sv, float* sv_out, hipStream_t st) {
+    const int esz = dtype == SMTM_F16 ? 2 : 4;
+    const int64_t ch_bytes = (int64_t)HW * esz;
+    const int64_t frame_bytes = ch_bytes * C;
+    if (ch_bytes % 16 == 0) {
+        if (dtype == SMTM_F16) launch_direct<_Float16, 16>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        else launch_direct<float, 16>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        return "d16";
+    }
+    if (ch_bytes % 8 == 0) {
+        if (dtype == SMTM_F16) launch_direct<_Float16, 8>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        else launch_direct<float, 8>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        return "d8";
+    }
+    if (frame_bytes % 16 == 0 && ch_bytes <= 256) {
+        const int tile_bytes = 64 * (int)ch_bytes;                 // multiple of 16 since 64*esz is
+        const int gpf = (C + 63) / 64, bpf = (gpf + 3) / 4;
+        const int grid = encode_grid((int64_t)max_rows * bpf, 1);
+        const size_t lds = (size_t)tile_bytes * 4;
+        if (dtype == SMTM_F16)
+            hipLaunchKernelGGL((k_encode_lds<_Float16, 8>), dim3(grid), dim3(256), lds, st,
+                               static_cast<const _Float16*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW);
+        else
+            hipLaunchKernelGGL((k_encode_lds<float, 8>), dim3(grid), dim3(256), lds, st,
+                               static_cast<const float*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW);
+        return "lds";
+    }
+    if (ch_bytes % 4 == 0) {
+        if (dtype == SMTM_F16) launch_direct<_Float16, 4>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        else launch_direct<float, 4>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        return "d4";
+    }
+    launch_direct<_Float16, 2>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+    return "d2";
+}
+
+}  // namespace smtm

@@ -1,0 +1,77 @@
+// Internal declarations shared by the host runtime (api.hip) and the kernel files.
+// Nothing here crosses the C ABI declared in include/smtm.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/smtm.h"
+
+namespace smtm {
+
+// Device-resident counters.  Kernels read the live count from here, so no launch ever waits
+// for the host to learn how many frames are left.
+struct Counts {
+    int32_t n_live;                       // live frames entering the next exit point
+    int32_t n_exit;                       // frames released by the last smtm_exit_compact
+    int32_t hot_k;                        // current fast-memory size
+    int32_t ticket;                       // spare
+    int32_t stats[SMTM_MAX_EXITS][4];     // per exit point: live in, released tier 1, released tier 2, spare
+};
+
+constexpr int kWave = 64;
+constexpr int kKPad = 64;                 // fp16 operand rows are zero-padded to a multiple of this many columns
+constexpr int kRowPad = 128;              // fp16 operand matrices are padded to a multiple of this many rows
+
+static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// ---- encode.hip -------------------------------------------------------------------------
+// Picks the streaming path from the shape; returns a short name of the path ("d16", "d8", "lds", "d4", "d2").
+const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
+                          const int32_t* frame_ids, const Counts* counts, int max_rows,
+                          float* sv_by_frame, float* sv_out_by_slot, hipStream_t st);
+
+// ---- lookup.hip -------------------------------------------------------------------------
+void launch_centre_prepare(const float* centres, int n, int C, float* cinv, _Float16* chat, int Cp,
+                           int row_lo, int row_hi, hipStream_t st);
+void launch_rownorm(const float* sv_by_frame, const int32_t* frame_ids, const Counts* counts,
+                    int max_rows, int C, float* vinv, _Float16* vhat, int Cp, hipStream_t st);
+void launch_score_fp32(const float* sv_by_frame, const int32_t* frame_ids, const Counts* counts,
+                       int max_rows, const float* vinv, const float* centres, const float* cinv,
+                       int n, int C, float weight, float* SA, float* sims_out, hipStream_t st);
+void launch_score_mfma(const _Float16* vhat, const _Float16* chat, int Cp, const int32_t* frame_ids,
+                       const Counts* counts, int max_rows, int n, float weight, float* SA,
+                       float* sims_out, hipStream_t st);
+void launch_top2_decide(const float* SA, const int32_t* frame_ids, const Counts* counts, int max_rows,
+                        int n, const uint8_t* in_hot, int tiers, float tau, int32_t* decision,
+                        int32_t* label, float* top_val, int32_t* top_id, float* top_val_user,
+                        int32_t* top_id_user, hipStream_t st);
+
+// ---- compact.hip ------------------------------------------------------------------------
+void launch_begin_batch(float* SA, int n, int batch, int32_t* live, int32_t* res_layer,
+                        int32_t* res_label, int32_t* res_tier, Counts* counts, hipStream_t st);
+void launch_compact(const int32_t* decision, const int32_t* label, const int32_t* frame_ids,
+                    int32_t* next_ids, int32_t* next_slots, Counts* counts, int exit_index,
+                    int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier, int32_t* n_exit_dev,
+                    int32_t* live_ids_user, int32_t* n_live_dev, int32_t* res_layer,
+                    int32_t* res_label, int32_t* res_tier, hipStream_t st);
+void launch_gather_rows(const void* src, const int32_t* row_ids, const int32_t* next_slots,
+                        const Counts* counts, int max_rows, void* dst, int64_t row_bytes,
+                        hipStream_t st);
+void launch_copy_i32(const int32_t* src, int32_t* dst, int count, hipStream_t st);
+void launch_set_hot(const int32_t* ids, int k, int n, int32_t* hot_ids, uint8_t* in_hot, Counts* counts,
+                    hipStream_t st);
+void launch_fill_u32(uint32_t* dst, uint32_t value, int count, hipStream_t st);
+
+// ---- update.hip -------------------------------------------------------------------------
+void launch_tables_update(const int32_t* label, int batch, int n, uint32_t* FT, uint32_t* TS,
+                          uint32_t* cls_cnt, int32_t* cls_last, hipStream_t st);
+void launch_centres_update(float* centres, uint32_t* mcount, float* cinv, _Float16* chat, int Cp,
+                           const float* sv_by_frame, int C, int n, int exit_index /*0-based*/,
+                           const int32_t* label, const int32_t* stop_layer, int batch,
+                           const uint32_t* cls_cnt, hipStream_t st);
+void launch_policy(const uint32_t* FT, const uint32_t* TS, int n, uint32_t W, uint32_t cl_num,
+                   uint32_t cl_den, int hot_min, int hot_max, uint64_t* score, int32_t* order,
+                   int32_t* hot_ids, uint8_t* in_hot, Counts* counts, hipStream_t st);
+
+}  // namespace smtm

@@ -1,0 +1,354 @@
+// Lookup: cosine similarity of every live frame's semantic vector with every class centre
+// (arXiv 2112.02644, Eq. 1), accumulation over exit points with weight 2^(l-1) (Eq. 3), and per
+// memory tier the highest / second-highest accumulated similarity with the exit rule of Eq. 4.
+//
+// Everything read here (semantic vectors, centres, SA) is a few MB and stays in L2; the only
+// dense contraction is [live frames] x [classes] x [channels], which runs on the matrix cores
+// with unit-normalised fp16 operands and fp32 accumulation, or in fp32 vector arithmetic when
+// the feature maps are fp32.
+#include "internal.h"
+
+namespace smtm {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float wave_sum(float x) {
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+__device__ __forceinline__ float inv_norm_of(float nrm2) {
+    // 0 marks a vector with zero or non-finite length: its similarities are defined as 0.
+    if (!(nrm2 > 0.f) || !(nrm2 < __builtin_inff())) return 0.f;
+    return 1.0f / sqrtf(nrm2);
+}
+
+// One wavefront per class: 1/|SC_j| and the unit-normalised fp16 copy [n_pad, Cp] (zero padded).
+__global__ __launch_bounds__(256) void k_centre_prepare(const float* __restrict__ centres, int n, int C,
+                                                        float* __restrict__ cinv,
+                                                        _Float16* __restrict__ chat, int Cp,
+                                                        int row_lo, int row_hi) {
+    const int lane = threadIdx.x & 63;
+    const int j = row_lo + blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= row_hi) return;
+    if (j >= n) {                                       // padding rows of the fp16 copy
+        for (int c = lane; c < Cp; c += 64) chat[(int64_t)j * Cp + c] = (_Float16)0.f;
+        return;
+    }
+    const float* p = centres + (int64_t)j * C;
+    float ss = 0.f;
+    for (int c = lane; c < C; c += 64) { const float x = p[c]; ss += x * x; }
+    ss = wave_sum(ss);
+    const float inv = inv_norm_of(ss);
+    if (lane == 0) cinv[j] = inv;
+    for (int c = lane; c < Cp; c += 64) {
+        float x = 0.f;
+        if (c < C && inv != 0.f) x = p[c] * inv;
+        chat[(int64_t)j * Cp + c] = (_Float16)x;
+    }
+}
+
+void launch_centre_prepare(const float* centres, int n, int C, float* cinv, _Float16* chat, int Cp,
+                           int row_lo, int row_hi, hipStream_t st) {
+    const int rows = row_hi - row_lo;
+    if (rows <= 0) return;
+    hipLaunchKernelGGL(k_centre_prepare, dim3((rows + 3) / 4), dim3(256), 0, st, centres, n, C, cinv,
+                       chat, Cp, row_lo, row_hi);
+}
+
+// One wavefront per live slot: 1/|SV| and (optionally) the unit-normalised fp16 row for the MFMA path.
+__global__ __launch_bounds__(256) void k_rownorm(const float* __restrict__ sv,
+                                                 const int32_t* __restrict__ frame_ids,
+                                                 const Counts* __restrict__ counts, int max_rows, int C,
+                                                 float* __restrict__ vinv, _Float16* __restrict__ vhat,
+                                                 int Cp) {
+    const int lane = threadIdx.x & 63;
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    const int n_waves = gridDim.x * 4;
+    for (int slot = blockIdx.x * 4 + (threadIdx.x >> 6); slot < n_live; slot += n_waves) {
+        const float* p = sv + (int64_t)frame_ids[slot] * C;
+        float ss = 0.f;
+        for (int c = lane; c < C; c += 64) { const float x = p[c]; ss += x * x; }
+        ss = wave_sum(ss);
+        const float inv = inv_norm_of(ss);
+        if (lane == 0) vinv[slot] = inv;
+        if (vhat) {
+            for (int c = lane; c < Cp; c += 64) {
+                float x = 0.f;
+                if (c < C && inv != 0.f) x = p[c] * inv;
+                vhat[(int64_t)slot * Cp + c] = (_Float16)x;
+            }
+        }
+    }
+}
+
+void launch_rownorm(const float* sv, const int32_t* frame_ids, const Counts* counts, int max_rows,
+                    int C, float* vinv, _Float16* vhat, int Cp, hipStream_t st) {
+    int grid = (max_rows + 3) / 4;
+    if (grid > 2048) grid = 2048;
+    hipLaunchKernelGGL(k_rownorm, dim3(grid), dim3(256), 0, st, sv, frame_ids, counts, max_rows, C, vinv,
+                       vhat, Cp);
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32 scoring: 64 slots x 64 classes per block, 4 x 4 per thread, K staged through LDS.
+// s = <SV, SC_j> * (1/|SV|) * (1/|SC_j|);  SA[frame][j] += weight * s.
+constexpr int FT_M = 64, FT_N = 64, FT_K = 16;
+
+__global__ __launch_bounds__(256) void k_score_fp32(
+    const float* __restrict__ sv, const int32_t* __restrict__ frame_ids,
+    const Counts* __restrict__ counts, int max_rows, const float* __restrict__ vinv,
+    const float* __restrict__ centres, const float* __restrict__ cinv, int n, int C, float weight,
+    float* __restrict__ SA, float* __restrict__ sims_out) {
+    __shared__ float As[FT_K][FT_M + 4];
+    __shared__ float Bs[FT_K][FT_N + 4];
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    const int m0 = blockIdx.y * FT_M, n0 = blockIdx.x * FT_N;
+    if (m0 >= n_live) return;                            // uniform over the block
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int lr = tid >> 2, lk = (tid & 3) * 4;         // loader: row 0..63, k offset 0,4,8,12
+    const int a_slot = m0 + lr, b_cls = n0 + lr;
+    const float* a_ptr = a_slot < n_live ? sv + (int64_t)frame_ids[a_slot] * C : nullptr;
+    const float* b_ptr = b_cls < n ? centres + (int64_t)b_cls * C : nullptr;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < C; k0 += FT_K) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = k0 + lk + i;
+            As[lk + i][lr] = (a_ptr && k < C) ? a_ptr[k] : 0.f;
+            Bs[lk + i][lr] = (b_ptr && k < C) ? b_ptr[k] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < FT_K; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int slot = m0 + ty * 4 + i;
+        if (slot >= n_live) continue;
+        const float vi = vinv[slot];
+        const int64_t frame = frame_ids[slot];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int cls = n0 + tx * 4 + j;
+            if (cls >= n) continue;
+            const float ci = cinv[cls];
+            float s = acc[i][j] * vi * ci;
+            if (vi == 0.f || ci == 0.f || !(fabsf(s) < __builtin_inff())) s = 0.f;
+            SA[frame * n + cls] += weight * s;
+            if (sims_out) sims_out[(int64_t)slot * n + cls] = s;
+        }
+    }
+}
+
+void launch_score_fp32(const float* sv, const int32_t* frame_ids, const Counts* counts, int max_rows,
+                       const float* vinv, const float* centres, const float* cinv, int n, int C,
+                       float weight, float* SA, float* sims_out, hipStream_t st) {
+    dim3 grid((n + FT_N - 1) / FT_N, (max_rows + FT_M - 1) / FT_M);
+    hipLaunchKernelGGL(k_score_fp32, grid, dim3(256), 0, st, sv, frame_ids, counts, max_rows, vinv,
+                       centres, cinv, n, C, weight, SA, sims_out);
+}
+
+// ---------------------------------------------------------------------------------------------
+// MFMA scoring.  A = unit fp16 semantic vectors by slot [rows_pad, Cp], B = unit fp16 centres
+// [n_pad, Cp], both K-contiguous and zero padded, so S = A * B^T needs no bounds checks inside
+// the K loop.  Block = 4 wavefronts as 2 x 2, each wavefront one 32x32 tile per (WM, WN) repeat,
+// v_mfma_f32_32x32x16_f16: lane holds A[row = lane%32][k = 8*(lane/32) .. +7] and the same for
+// B by column; acc[i] is C[row = 8*(i/4) + 4*(lane/32) + i%4][col = lane%32].
+constexpr int MF_K = 64;                 // K per LDS stage
+constexpr int MF_LD = MF_K + 8;          // padded LDS row (halves): 144 B keeps 16-byte reads conflict-free
+
+template <int WM, int WN>
+__global__ __launch_bounds__(256) void k_score_mfma(
+    const _Float16* __restrict__ A, const _Float16* __restrict__ B, int Cp,
+    const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows, int n,
+    float weight, float* __restrict__ SA, float* __restrict__ sims_out) {
+    constexpr int BM = 64 * WM, BN = 64 * WN;
+    __shared__ _Float16 As[BM * MF_LD];
+    __shared__ _Float16 Bs[BN * MF_LD];
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    if (m0 >= n_live) return;                            // uniform over the block
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lk = (lane >> 5) * 8;
+
+    floatx16 acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // loader: each 64-half row of a stage is 8 chunks of 16 B; thread -> (row, chunk)
+    const int ld_row = tid >> 3, ld_chunk = tid & 7;
+    for (int k0 = 0; k0 < Cp; k0 += MF_K) {
+#pragma unroll
+        for (int r = 0; r < BM; r += 32) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(A + (int64_t)(m0 + r + ld_row) * Cp + k0 + ld_chunk * 8);
+            *reinterpret_cast<u32x4*>(&As[(r + ld_row) * MF_LD + ld_chunk * 8]) = v;
+        }
+#pragma unroll
+        for (int r = 0; r < BN; r += 32) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(B + (int64_t)(n0 + r + ld_row) * Cp + k0 + ld_chunk * 8);
+            *reinterpret_cast<u32x4*>(&Bs[(r + ld_row) * MF_LD + ld_chunk * 8]) = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < MF_K; ks += 16) {
+            half8_t a[WM], b[WN];
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+                a[i] = *reinterpret_cast<const half8_t*>(&As[((wm * WM + i) * 32 + lrow) * MF_LD + ks + lk]);
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+                b[j] = *reinterpret_cast<const half8_t*>(&Bs[((wn * WN + j) * 32 + lrow) * MF_LD + ks + lk]);
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            const int cls = n0 + (wn * WN + j) * 32 + (lane & 31);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int slot = m0 + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                if (slot < n_live && cls < n) {
+                    const float s = acc[i][j][e];
+                    const int64_t frame = frame_ids[slot];
+                    SA[frame * n + cls] += weight * s;
+                    if (sims_out) sims_out[(int64_t)slot * n + cls] = s;
+                }
+            }
+        }
+}
+
+void launch_score_mfma(const _Float16* vhat, const _Float16* chat, int Cp, const int32_t* frame_ids,
+                       const Counts* counts, int max_rows, int n, float weight, float* SA,
+                       float* sims_out, hipStream_t st) {
+    // operands are padded to kRowPad rows, so a 64x64 block tile never reads outside them
+    dim3 grid((n + 63) / 64, (max_rows + 63) / 64);
+    hipLaunchKernelGGL((k_score_mfma<1, 1>), grid, dim3(256), 0, st, vhat, chat, Cp, frame_ids, counts,
+                       max_rows, n, weight, SA, sims_out);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Top-2 per tier and the exit rule.  One wavefront per live slot walks its SA row.
+struct Top2 {
+    float v1; int id1; float v2;
+};
+
+__device__ __forceinline__ bool better(float v, int id, float w, int jd) {
+    // (larger value first, then smaller class id); id < 0 marks "no entry"
+    if (jd < 0) return id >= 0;
+    if (id < 0) return false;
+    return v > w || (v == w && id < jd);
+}
+
+__device__ __forceinline__ void top2_push(Top2& t, float v, int id) {
+    if (better(v, id, t.v1, t.id1)) {
+        if (t.id1 >= 0) t.v2 = t.v1;
+        t.v1 = v; t.id1 = id;
+    } else if (v > t.v2) {
+        t.v2 = v;
+    }
+}
+
+__device__ __forceinline__ void top2_merge(Top2& t, float v1, int id1, float v2) {
+    // merge another (best, id, second) triple; the second of a triple never exceeds its best
+    if (better(v1, id1, t.v1, t.id1)) {
+        const float loser = t.id1 >= 0 ? t.v1 : -__builtin_inff();
+        t.v2 = fmaxf(v2, loser);
+        t.v1 = v1; t.id1 = id1;
+    } else if (id1 >= 0) {
+        t.v2 = fmaxf(t.v2, v1);
+    }
+}
+
+__device__ __forceinline__ bool exit_rule(float h, float sh, float tau) {
+    if (!(h > 0.f)) return false;
+    if (sh == -__builtin_inff()) return false;           // fewer than two entries in the tier
+    const float runner = sh > 0.f ? sh : 0.f;
+    return (h - sh) > tau * runner;
+}
+
+__global__ __launch_bounds__(256) void k_top2_decide(
+    const float* __restrict__ SA, const int32_t* __restrict__ frame_ids,
+    const Counts* __restrict__ counts, int max_rows, int n, const uint8_t* __restrict__ in_hot,
+    int tiers, float tau, int32_t* __restrict__ decision, int32_t* __restrict__ label,
+    float* __restrict__ top_val, int32_t* __restrict__ top_id, float* __restrict__ top_val_user,
+    int32_t* __restrict__ top_id_user) {
+    const int lane = threadIdx.x & 63;
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    const int n_waves = gridDim.x * 4;
+    const float ninf = -__builtin_inff();
+    for (int slot = blockIdx.x * 4 + (threadIdx.x >> 6); slot < n_live; slot += n_waves) {
+        const float* row = SA + (int64_t)frame_ids[slot] * n;
+        Top2 hot = {ninf, -1, ninf}, all = {ninf, -1, ninf};
+        for (int j = lane; j < n; j += 64) {
+            const float x = row[j];
+            top2_push(all, x, j);
+            if (in_hot[j]) top2_push(hot, x, j);
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            float v1 = __shfl_xor(all.v1, off, 64); int id1 = __shfl_xor(all.id1, off, 64);
+            float v2 = __shfl_xor(all.v2, off, 64);
+            top2_merge(all, v1, id1, v2);
+            v1 = __shfl_xor(hot.v1, off, 64); id1 = __shfl_xor(hot.id1, off, 64);
+            v2 = __shfl_xor(hot.v2, off, 64);
+            top2_merge(hot, v1, id1, v2);
+        }
+        if (lane == 0) {
+            int d = 0, lab = -1;
+            if (exit_rule(hot.v1, hot.v2, tau)) { d = 1; lab = hot.id1; }
+            else if (tiers == 2 && exit_rule(all.v1, all.v2, tau)) { d = 2; lab = all.id1; }
+            if (tiers != 2) { all.v1 = ninf; all.v2 = ninf; all.id1 = -1; }
+            decision[slot] = d;
+            label[slot] = lab;
+            float* tv = top_val + (int64_t)slot * 4;
+            tv[0] = hot.v1; tv[1] = hot.v2; tv[2] = all.v1; tv[3] = all.v2;
+            top_id[slot * 2] = hot.id1; top_id[slot * 2 + 1] = all.id1;
+            if (top_val_user) {
+                float* u = top_val_user + (int64_t)slot * 4;
+                u[0] = hot.v1; u[1] = hot.v2; u[2] = all.v1; u[3] = all.v2;
+            }
+            if (top_id_user) { top_id_user[slot * 2] = hot.id1; top_id_user[slot * 2 + 1] = all.id1; }
+        }
+    }
+}
+
+void launch_top2_decide(const float* SA, const int32_t* frame_ids, const Counts* counts, int max_rows,
+                        int n, const uint8_t* in_hot, int tiers, float tau, int32_t* decision,
+                        int32_t* label, float* top_val, int32_t* top_id, float* top_val_user,
+                        int32_t* top_id_user, hipStream_t st) {
+    int grid = (max_rows + 3) / 4;
+    if (grid > 2048) grid = 2048;
+    hipLaunchKernelGGL(k_top2_decide, grid, dim3(256), 0, st, SA, frame_ids, counts, max_rows, n, in_hot,
+                       tiers, tau, decision, label, top_val, top_id, top_val_user, top_id_user);
+}
+
+}  // namespace smtm

@@ -1,0 +1,410 @@
+"""GPU parity tests: the HIP library, called through its C ABI, against the CPU oracle on the
+same seeded inputs.  Sizes span several tiles and ragged tails; the ResNet-50- and
+MobileNetV2-shaped workloads run at their full sizes."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import smtm_oracle as O
+from paper_2112_02644_amd import Smtm, SmtmConfig, SmtmError, SCORE_AUTO, SCORE_FP32, SCORE_MFMA
+from workloads import configs, streams
+
+import parity as P
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _one_batch(w, *, tau=None, tiers=None, mode="row_ids", fused=False, score_path=SCORE_AUTO,
+               check_sims=True, batch_index=0):
+    cents = streams.centroids(w)
+    ls = streams.labels(w, max(w.batch * (batch_index + 1), w.batch))
+    fm = streams.batch_feature_maps(w, cents, ls, batch_index, DEV)
+    tau = w.tau if tau is None else tau
+    ctx = P.make_ctx(w, cents, ls.initial_hot, tau=tau, tiers=tiers, score_path=score_path)
+    mem = P.make_oracle(w, cents, ls.initial_hot, tau=tau, tiers=tiers)
+    rep = P.check_batch(ctx, mem, w, fm, tau=tau, rtol=P.sim_rtol(w, score_path), mode=mode, fused=fused,
+                        check_sims=check_sims)
+    ctx.close()
+    return rep, ls
+
+
+# ------------------------------------------------------------------ encode alone, many shapes
+
+ENCODE_SHAPES = [
+    # (dtype, rows, C, H, W)  -> path
+    (torch.float16, 5, 7, 56, 56),     # d16, g = 64, ragged last iteration
+    (torch.float16, 3, 9, 28, 28),     # d16, g = 16, C not a multiple of the 4 channels per wavefront
+    (torch.float16, 6, 13, 14, 14),    # d8
+    (torch.float16, 4, 136, 7, 7),     # lds, 2 full groups + tail of 8 channels (784 B)
+    (torch.float16, 4, 24, 7, 7),      # lds, single short group
+    (torch.float16, 3, 3, 7, 7),       # frame bytes not a multiple of 16 -> d2
+    (torch.float16, 3, 6, 5, 5),       # 50-byte channels, frame 300 B -> d2
+    (torch.float16, 2, 5, 112, 112),   # d16, more chunks than one unrolled pass
+    (torch.float16, 7, 4, 1, 1),       # H*W = 1
+    (torch.float16, 2, 40, 3, 3),      # 18-byte channels, 720-byte frames -> lds
+    (torch.float32, 5, 10, 14, 14),    # d16 fp32
+    (torch.float32, 3, 4, 5, 5),       # 100-byte channels, 400-byte frames -> lds fp32
+    (torch.float32, 3, 5, 3, 3),       # 36-byte channels, 180-byte frames -> d4
+    (torch.float32, 2, 6, 7, 6),       # 168-byte channels -> d8
+    (torch.float16, 70, 64, 7, 7),     # more frames than one pass of a small grid
+]
+
+
+@pytest.mark.parametrize("dtype,rows,C,H,W", ENCODE_SHAPES)
+@pytest.mark.parametrize("use_ids", [False, True])
+def test_encode_shapes(dtype, rows, C, H, W, use_ids):
+    _say("encode", dtype, rows, C, H, W, use_ids)
+    g = torch.Generator().manual_seed(rows * 1000 + C)
+    F = (torch.randn(rows, C, H, W, generator=g) * 2 + 0.25).to(dtype)
+    F[0, 0] = 3.0                                         # a constant map pools to itself exactly
+    Fd = F.to(DEV)
+    batch = rows if not use_ids else max(2, rows - 1)
+    ctx = Smtm(SmtmConfig(n_classes=4, dims=[C], max_batch=rows, hot_init=2))
+    ctx.begin_batch(batch)
+    sv = torch.full((rows, C), float("nan"), device=DEV)
+    ids = None
+    if use_ids:
+        perm = np.random.default_rng(C).permutation(rows)[:batch].astype(np.int32)
+        ids = torch.from_numpy(perm).to(DEV)
+    ctx.encode(1, Fd, row_ids=ids, sv_out=sv)
+    torch.cuda.synchronize()
+    ref = O.encode(F.numpy(), row_ids=None if ids is None else perm, n_live=batch)
+    got = sv[:batch].cpu().numpy().astype(np.float64)
+    rows_read = np.arange(batch) if ids is None else perm
+    scale = np.maximum(np.abs(ref), F.float().abs().mean(dim=(2, 3)).numpy()[rows_read])
+    assert (np.abs(got - ref) / scale).max() <= P.SV_RTOL
+    assert torch.isnan(sv[batch:]).all()
+    if ids is None or 0 in perm:
+        r0 = 0 if ids is None else int(np.flatnonzero(perm == 0)[0])
+        assert got[r0, 0] == 3.0
+    ctx.close()
+
+
+def test_encode_special_values():
+    F = torch.zeros(4, 8, 7, 7, dtype=torch.float16)
+    F[1] = 65504.0                                        # largest fp16: the fp32 sum must not overflow or lose it
+    F[2, 3, 2, 2] = float("inf")
+    F[3, 1, 0, 0] = 6e-8                                  # fp16 subnormal
+    ctx = Smtm(SmtmConfig(n_classes=4, dims=[8], max_batch=4, hot_init=2))
+    ctx.begin_batch(4)
+    sv = torch.zeros(4, 8, device=DEV)
+    ctx.encode(1, F.to(DEV), sv_out=sv)
+    torch.cuda.synchronize()
+    got = sv.cpu().numpy()
+    ref = O.encode(F.numpy())
+    assert np.all(got[0] == 0) and np.all(got[1] == 65504.0)
+    assert np.isinf(got[2, 3]) and np.all(got[2, :3] == 0)
+    assert abs(got[3, 1] - ref[3, 1]) <= 1e-5 * ref[3, 1]
+    ctx.close()
+
+
+# ------------------------------------------------------------------ workload 1: Tiny (fp32)
+
+@pytest.mark.parametrize("tau", [0.0, 0.25, 1.0, 4.0, 16.0])
+@pytest.mark.parametrize("tiers", [1, 2])
+def test_tiny_tau_sweep(tau, tiers):
+    _say("tiny", tau, tiers)
+    rep, _ = _one_batch(configs.TINY, tau=tau, tiers=tiers)
+    assert rep.max_sim_err <= 1.0 and rep.in_band_flips == 0
+    if tiers == 1:
+        assert rep.tier_hist[2] == 0
+
+
+@pytest.mark.parametrize("mode,fused", [("dense", False), ("row_ids", True), ("dense", True)])
+def test_tiny_modes(mode, fused):
+    _say("tiny", mode, fused)
+    rep, _ = _one_batch(configs.TINY, mode=mode, fused=fused)
+    assert sum(rep.exit_hist) == configs.TINY.batch
+
+
+def test_tiny_mfma_path_on_fp32_maps_within_fp16_tolerance():
+    rep, _ = _one_batch(configs.TINY, score_path=SCORE_MFMA)
+    assert rep.max_sim_err <= 1.0
+
+
+# ------------------------------------------------------------------ workload 2: ResNet-18-shaped
+
+@pytest.mark.parametrize("mode,fused,path", [("row_ids", False, SCORE_AUTO), ("dense", False, SCORE_AUTO),
+                                             ("row_ids", True, SCORE_AUTO), ("row_ids", False, SCORE_FP32)])
+def test_resnet18(mode, fused, path):
+    _say("resnet18", mode, fused, path)
+    w = configs.RESNET18
+    rep, _ = _one_batch(w, mode=mode, fused=fused, score_path=path)
+    _say("  exit histogram", rep.exit_hist, "tiers", rep.tier_hist, "in-band", rep.in_band_frames,
+         "flips", rep.in_band_flips, "max sim err (x tol)", rep.max_sim_err)
+    assert sum(rep.exit_hist) == w.batch
+    assert rep.in_band_flips <= max(2, w.batch // 50)
+
+
+@pytest.mark.parametrize("tau", [0.0, 1.0, 16.0, 1e6])
+def test_resnet18_tau_sweep(tau):
+    _say("resnet18 tau", tau)
+    w = configs.RESNET18
+    rep, _ = _one_batch(w, tau=tau, check_sims=False)
+    if tau >= 1e6:
+        # only frames whose runner-up is not positively correlated can exit
+        _say("  exits at tau=1e6:", rep.exit_hist)
+    assert sum(rep.exit_hist) == w.batch
+
+
+# ------------------------------------------------------------------ workloads 3 and 4 at full size
+
+def test_resnet50_full_size():
+    w = configs.RESNET50
+    _say("resnet50 full size")
+    rep, ls = _one_batch(w)
+    _say("  exit histogram", rep.exit_hist, "tiers", rep.tier_hist, "in-band", rep.in_band_frames,
+         "flips", rep.in_band_flips, "max sim err (x tol)", rep.max_sim_err, "max sv err", rep.max_sv_err)
+    assert sum(rep.exit_hist) == w.batch
+    assert rep.in_band_flips <= w.batch // 50
+    # off-memory frames (about 30%) mostly run to the end; in-memory frames mostly exit
+    off = (ls.label[: w.batch] < 0).mean()
+    assert 0.1 < off < 0.5
+    assert rep.exit_hist[0] >= 0.5 * off * w.batch
+
+
+def test_resnet50_fused_dense_full_size():
+    w = configs.RESNET50
+    _say("resnet50 fused dense")
+    rep, _ = _one_batch(w, mode="dense", fused=True, check_sims=False)
+    assert sum(rep.exit_hist) == w.batch
+
+
+def test_mobilenetv2_full_size():
+    w = configs.MOBILENETV2
+    _say("mobilenetv2 full size")
+    rep, _ = _one_batch(w)
+    _say("  exit histogram", rep.exit_hist, "tiers", rep.tier_hist, "in-band", rep.in_band_frames,
+         "flips", rep.in_band_flips, "max sim err (x tol)", rep.max_sim_err)
+    assert sum(rep.exit_hist) == w.batch
+    assert rep.in_band_flips <= w.batch // 50
+
+
+# ------------------------------------------------------------------ workload 5: adaptive stream
+
+def _run_stream(w, n_batches, check_every=1):
+    cents = streams.centroids(w)
+    ls = streams.labels(w, w.batch * n_batches)
+    ctx = P.make_ctx(w, cents, ls.initial_hot)
+    mem = P.make_oracle(w, cents, ls.initial_hot)
+    rep = P.ParityReport()
+    worst_centre = 0.0
+    for b in range(n_batches):
+        fm = streams.batch_feature_maps(w, cents, ls, b, DEV)
+        P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), check_sims=(b == 0), report=rep)
+        # frames that ran to the end get the stream's own label (stand-in for the classifier),
+        # but do not move centres: only exited classes are updated
+        truth = ls.label[b * w.batch:(b + 1) * w.batch]
+        label = np.where(mem.exit_layer > 0, mem.label, truth).astype(np.int32)
+        stop = mem.exit_layer.astype(np.int32)
+        upd, e = P.check_cache_update(ctx, mem, label, stop)
+        worst_centre = max(worst_centre, e)
+        rep.hot_sizes.append(len(mem.hot_ids))
+        _say(f"  batch {b}: exits {rep.exit_hist} hot size {len(mem.hot_ids)} (unclamped {upd['k_unclamped']})"
+             f" flips {rep.in_band_flips} centre err {e:.2e}")
+    ctx.close()
+    return rep, worst_centre
+
+
+def test_adaptive_stream_short_with_drift():
+    # the stream of workload 5 shortened so that it drifts inside the test: 10 batches of 512,
+    # most probable classes re-drawn every 2048 frames, window of 1024 frames
+    w = dataclasses.replace(configs.ADAPTIVE, total_frames=512 * 10, drift_every=2048)
+    _say("adaptive short")
+    rep, worst = _run_stream(w, 10)
+    assert rep.frames == 5120
+    assert min(rep.hot_sizes) >= w.hot_min and max(rep.hot_sizes) <= w.hot_max
+    assert len(set(rep.hot_sizes)) > 1                    # the fast memory did change size
+    assert rep.in_band_flips <= rep.frames // 50
+
+
+def test_adaptive_partial_last_batch():
+    # a stream whose last batch is short (as 100,000 = 195 x 512 + 160)
+    w = dataclasses.replace(configs.ADAPTIVE, batch=96, exits=((32, 28, 28), (64, 14, 14), (64, 7, 7)),
+                            n_classes=50, hot=8, hot_min=4, hot_max=32, window=64, total_frames=96 * 3 + 40,
+                            drift_every=128, drift_top=5)
+    cents = streams.centroids(w)
+    ls = streams.labels(w)
+    ctx = P.make_ctx(w, cents, ls.initial_hot)
+    mem = P.make_oracle(w, cents, ls.initial_hot)
+    rep = P.ParityReport()
+    for b in range(4):
+        fm = streams.batch_feature_maps(w, cents, ls, b, DEV)
+        assert fm[0].shape[0] == (96 if b < 3 else 40)
+        P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), report=rep)
+        truth = ls.label[b * 96:b * 96 + fm[0].shape[0]]
+        label = np.where(mem.exit_layer > 0, mem.label, truth).astype(np.int32)
+        P.check_cache_update(ctx, mem, label, mem.exit_layer.astype(np.int32))
+    assert rep.frames == 328
+    ctx.close()
+
+
+# ------------------------------------------------------------------ cache update alone
+
+def test_cache_update_random_tables():
+    rng = np.random.default_rng(3)
+    n, dims, B = 300, [24, 40], 700
+    cents = [torch.randn(n, c) for c in dims]
+    w = dataclasses.replace(configs.ADAPTIVE, n_classes=n, exits=((24, 2, 2), (40, 2, 2)), batch=B, hot=10,
+                            hot_min=5, hot_max=200, window=50, init_count=3)
+    hot0 = np.arange(10, dtype=np.int32)
+    ctx = P.make_ctx(w, cents, hot0)
+    mem = P.make_oracle(w, cents, hot0)
+    # cold start with nothing recognised: the fast memory stays as it is
+    ctx.begin_batch(B); mem.begin_batch(B)
+    upd, _ = P.check_cache_update(ctx, mem, np.full(B, -1, np.int32), np.zeros(B, np.int32))
+    assert upd["k"] == -1
+    for it in range(6):
+        Bi = B if it % 2 == 0 else 333
+        g = torch.Generator(device=DEV).manual_seed(100 + it)
+        fm = [torch.randn(Bi, c, 2, 2, device=DEV, generator=g).to(torch.float16) for c in dims]
+        P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), check_sims=False)
+        layer = mem.exit_layer
+        zipf = np.minimum(rng.zipf(1.3, Bi) - 1, n - 1)
+        label = np.where(rng.random(Bi) < 0.1, -1, rng.permutation(n)[zipf]).astype(np.int32)
+        reached = np.where(layer == 0, 2, layer)           # exit points at which this frame was encoded
+        stop = np.minimum(rng.integers(0, 3, Bi), reached).astype(np.int32)
+        P.check_cache_update(ctx, mem, label, stop)
+    ctx.close()
+
+
+def test_cache_update_saturating_tables_and_big_scores():
+    n = 64
+    w = dataclasses.replace(configs.ADAPTIVE, n_classes=n, exits=((8, 1, 1),), batch=16, hot=4, hot_min=2,
+                            hot_max=n, window=7)
+    cents = [torch.randn(n, 8)]
+    ctx = P.make_ctx(w, cents, np.arange(4, dtype=np.int32))
+    mem = P.make_oracle(w, cents, np.arange(4, dtype=np.int32))
+    ft = np.full(n, 2 ** 32 - 3, np.uint32); ts = np.zeros(n, np.uint32)
+    ts[::3] = 2 ** 32 - 5; ts[1::3] = 13
+    ctx.tables_import(ft, ts); mem.FT[:] = ft; mem.TS[:] = ts
+    ctx.begin_batch(16); mem.begin_batch(16)
+    label = np.array([5] * 9 + [-1, 7, 7, 63, 0, 0, 1], np.int32)
+    P.check_cache_update(ctx, mem, label, np.zeros(16, np.int32))
+    assert mem.FT[5] == 2 ** 32 - 1 and mem.TS[3] == 2 ** 32 - 1
+    ctx.close()
+
+
+# ------------------------------------------------------------------ edge cases of the batch path
+
+def test_all_frames_exit_then_empty_exits_and_none_exit():
+    w = dataclasses.replace(configs.RESNET18, batch=70, n_classes=20, hot=20, off_memory=0.0, sigma=0.05)
+    cents = streams.centroids(w); ls = streams.labels(w)
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    hot = np.arange(20, dtype=np.int32)
+    ctx = P.make_ctx(w, cents, hot, tau=0.5); mem = P.make_oracle(w, cents, hot, tau=0.5)
+    rep = P.check_batch(ctx, mem, w, fm, tau=0.5, rtol=P.sim_rtol(w))
+    assert rep.exit_hist[1] == 70 and rep.exit_hist[0] == 0      # everything leaves at exit 1; exits 2-4 see 0 frames
+    rep = P.check_batch(ctx, mem, w, fm, tau=0.5, rtol=P.sim_rtol(w), mode="dense", fused=True)
+    assert rep.exit_hist[1] == 70
+    # tau so large that nothing exits (all similarities to the runner-up are positive here or the rule fails)
+    rep = P.check_batch(ctx, mem, w, [f.abs() for f in fm], tau=1e30, rtol=P.sim_rtol(w), mode="dense")
+    _say("  none-exit histogram", rep.exit_hist)
+    ctx.close()
+
+
+def test_batch_of_one_and_two_classes():
+    w = dataclasses.replace(configs.TINY, batch=1, n_classes=2, hot=2)
+    rep, _ = _one_batch(w, tau=0.1)
+    assert rep.frames == 1
+
+
+def test_zero_and_nonfinite_frames_never_exit():
+    w = configs.TINY
+    cents = streams.centroids(w); ls = streams.labels(w)
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    fm[0][3] = 0.0                       # zero semantic vector: similarity 0 to everything
+    fm[0][5, 7, 2, 2] = float("inf")     # non-finite length
+    fm[0][9, 1, 0, 0] = float("nan")
+    ctx = P.make_ctx(w, cents, ls.initial_hot, tau=0.0); mem = P.make_oracle(w, cents, ls.initial_hot, tau=0.0)
+    P.check_batch(ctx, mem, w, fm, tau=0.0, rtol=P.sim_rtol(w), check_sims=False)
+    assert mem.exit_layer[3] == 0 and mem.exit_layer[5] == 0 and mem.exit_layer[9] == 0
+    ctx.close()
+
+
+def test_duplicate_centre_tie_label_is_smaller_id():
+    w = configs.TINY
+    cents = streams.centroids(w); ls = streams.labels(w)
+    cents[0][7] = cents[0][2]            # classes 2 and 7 identical: exact tie, never exits at tau = 0, best id = 2
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    hot = np.array([2, 7, 1, 0], np.int32)
+    ctx = P.make_ctx(w, cents, hot, tau=0.0); mem = P.make_oracle(w, cents, hot, tau=0.0)
+    P.check_batch(ctx, mem, w, fm, tau=0.0, rtol=P.sim_rtol(w))
+    tied = np.isin(ls.label, [2, 7])
+    assert tied.any() and np.all(mem.exit_layer[tied] == 0)
+    ctx.close()
+
+
+def test_two_runs_are_bit_identical():
+    w = configs.RESNET18
+    cents = streams.centroids(w); ls = streams.labels(w)
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    outs = []
+    for _ in range(2):
+        ctx = P.make_ctx(w, cents, ls.initial_hot)
+        ctx.begin_batch(w.batch)
+        keep = []
+        for l in range(1, 5):
+            sv = torch.zeros(w.batch, w.dims[l - 1], device=DEV)
+            tv = torch.zeros(w.batch, 2, 2, device=DEV); ti = torch.zeros(w.batch, 2, dtype=torch.int32, device=DEV)
+            sims = torch.zeros(w.batch, w.n_classes, device=DEV)
+            ctx.encode(l, fm[l - 1], row_ids=ctx.live_ids(), sv_out=sv)
+            ctx.lookup(l, top_val=tv, top_id=ti, sims_out=sims)
+            ctx.exit_compact(l)
+            keep += [sv, tv, ti, sims]
+        res = [torch.zeros(w.batch, dtype=torch.int32, device=DEV) for _ in range(3)]
+        ctx.batch_results(*res)
+        lab = res[1].clone(); stop = res[0].clone()
+        ctx.cache_update(lab, stop, w.batch)
+        torch.cuda.synchronize()
+        cen = [ctx.memory_export(l)[0] for l in range(1, 5)]
+        outs.append(([k.cpu() for k in keep + res], cen, ctx.tables_export()))
+        ctx.close()
+    for a, b in zip(outs[0][0], outs[1][0]):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+    for a, b in zip(outs[0][1], outs[1][1]):
+        assert np.array_equal(a.view(np.int32), b.view(np.int32))
+
+
+# ------------------------------------------------------------------ call-order and argument errors
+
+def test_call_order_and_argument_errors():
+    ctx = Smtm(SmtmConfig(n_classes=8, dims=[16, 16], max_batch=8, hot_init=4))
+    F = torch.zeros(8, 16, 2, 2, dtype=torch.float16, device=DEV)
+    with pytest.raises(SmtmError) as e:
+        ctx.encode(1, F)
+    assert e.value.code == 3                       # no batch begun
+    ctx.begin_batch(8)
+    with pytest.raises(SmtmError) as e:
+        ctx.lookup(1)
+    assert e.value.code == 3                       # lookup before encode
+    with pytest.raises(SmtmError) as e:
+        ctx.encode(3, F)
+    assert e.value.code == 1                       # exit point out of range
+    ctx.encode(1, F)
+    with pytest.raises(SmtmError) as e:
+        ctx.exit_compact(1)
+    assert e.value.code == 3                       # exit_compact before lookup
+    ctx.lookup(1)
+    with pytest.raises(SmtmError) as e:
+        ctx.exit_compact(1, fmap_in=F, fmap_out=F, row_bytes=128)
+    assert e.value.code == 1                       # gather in place
+    ctx.exit_compact(1)
+    with pytest.raises(SmtmError) as e:
+        ctx.begin_batch(9)
+    assert e.value.code == 2
+    with pytest.raises(SmtmError) as e:
+        ctx.hot_set(np.array([1, 1, 2, 3], np.int32))
+    assert e.value.code == 1
+    with pytest.raises(SmtmError) as e:
+        ctx.cache_update(torch.zeros(4, dtype=torch.int32, device=DEV), torch.zeros(4, dtype=torch.int32, device=DEV), 4)
+    assert e.value.code == 2
+    torch.cuda.synchronize()
+    ctx.close()
