@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+A step is one batch of the ResNet-50-shaped workload through every part of the path:
+begin_batch, then at each of the four exit points encode -> lookup -> exit/compact (with the
+survivors' feature maps gathered for the next block), then the per-frame results and the memory
+update.  Inputs (all four feature-map tensors, 3.08 GB) are resident in HBM before the clock
+starts; nothing is read back inside the timed region.
+
+Prints one JSON line.  `value` is frames/s over the timed steps.  `roofline` is for the dominant
+kernel (the fp16 16-byte streaming encode kernel that serves exit points 1 and 2), timed with
+events on the launch stream inside the timed region.  `cpu_baseline` is the CPU oracle on a
+bounded sample of the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--cpu-sample", type=int, default=1024, help="frames of the batch given to the CPU oracle")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (frames are independent, so more GPUs "
+              "would each take a share of the batch with the memory tables replicated)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2112_02644_amd import Smtm, SmtmConfig
+    from workloads import configs, streams
+
+    w = configs.BY_NAME[args.workload]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    B, L, n = w.batch, w.n_exits, w.n_classes
+    cents = streams.centroids(w)
+    ls = streams.labels(w, B)
+    fmaps = streams.batch_feature_maps(w, cents, ls, 0, dev)
+    gathers = [torch.empty_like(f) for f in fmaps]
+    hot_max = w.hot_max or w.hot
+    cfg = SmtmConfig(n_classes=n, dims=w.dims, max_batch=B, hot_init=w.hot,
+                     hot_min=w.hot_min if w.hot_max else w.hot, hot_max=hot_max, tiers=w.tiers, tau=w.tau,
+                     window=w.window, init_count=w.init_count)
+    ctx = Smtm(cfg)
+    for l, c in enumerate(cents, start=1):
+        ctx.memory_load(l, c.numpy())
+    ctx.hot_set(ls.initial_hot)
+
+    i32 = dict(dtype=torch.int32, device=dev)
+    res_layer = torch.zeros(B, **i32); res_label = torch.zeros(B, **i32); res_tier = torch.zeros(B, **i32)
+    total = args.steps + args.warmup
+    live_log = torch.zeros((total, L), **i32)              # survivors after each exit point, per step
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+          for _ in range(total)]
+    esz = w.esz
+    live_ptr0 = live_log.data_ptr()
+
+    def step(s: int):
+        ctx.begin_batch(B)
+        for l in range(1, L + 1):
+            F = fmaps[l - 1]
+            ids = ctx.live_ids()
+            a, b = ev[s][l - 1]
+            a.record()
+            ctx.encode(l, F, row_ids=ids)
+            b.record()
+            ctx.lookup(l)
+            ctx.exit_compact(l, n_live_dev=live_ptr0 + 4 * (s * L + l - 1), fmap_in=F, row_ids=ids,
+                             fmap_out=gathers[l - 1], row_bytes=F[0].numel() * esz)
+        ctx.batch_results(res_layer, res_label, res_tier)
+        ctx.cache_update(res_label, res_layer, B)
+
+    for s in range(args.warmup):
+        step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.warmup, total):
+        step(s)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    fps = B * args.steps / elapsed
+
+    # ---- what the timed steps did
+    live = live_log.cpu().numpy()[args.warmup:]            # [steps, L] survivors after exit l
+    entering = np.concatenate([np.full((args.steps, 1), B), live[:, :-1]], axis=1)   # live frames entering exit l
+    exits = entering - live
+    enc_ms = np.array([[ev[s][l][0].elapsed_time(ev[s][l][1]) for l in range(L)]
+                       for s in range(args.warmup, total)])
+    per_exit_bytes = np.array([c * h * wd * esz + c * 4 for c, h, wd in w.exits], dtype=np.float64)
+    enc_bytes = entering * per_exit_bytes[None, :]
+    # dominant kernel: the 16-byte-load fp16 encode kernel = every exit point whose channel is a multiple of 16 B
+    dom = [l for l, (c, h, wd) in enumerate(w.exits) if (h * wd * esz) % 16 == 0]
+    dom_bytes = enc_bytes[:, dom].sum() / (args.steps * len(dom))
+    dom_ms = enc_ms[:, dom].sum() / (args.steps * len(dom))
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    gat_bytes = live * (per_exit_bytes[None, :] - np.array([c * 4 for c, _, _ in w.exits])[None, :]) * 2.0
+    path_bytes = (enc_bytes.sum(axis=1) + gat_bytes.sum(axis=1)).mean()   # algorithmic bytes per step: encode stream + gather (read + write)
+    stage_gbs = path_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- CPU oracle on a bounded sample of the same batch (all host threads it gets)
+    from oracle import smtm_oracle as O
+    ns = min(args.cpu_sample, B)
+    host = [f[:ns].cpu().numpy() for f in fmaps]
+    mem = O.Memory([c.numpy() for c in cents], ls.initial_hot, tau=w.tau, tiers=w.tiers, window=w.window,
+                   hot_min=cfg.hot_min, hot_max=hot_max, init_count=w.init_count)
+    cores = O.get_max_threads()
+    t1 = time.perf_counter()
+    mem.begin_batch(ns)
+    for l in range(1, L + 1):
+        mem.stage(l, host[l - 1], row_ids=mem.live.copy())
+    mem.cache_update(mem.label, mem.exit_layer)
+    cpu_s = time.perf_counter() - t1
+
+    out = {
+        "metric": "frames/sec through encode+lookup+exit (ResNet-50 exits)" if w.name == "resnet50"
+                  else f"frames/sec through encode+lookup+exit ({w.name} exits)",
+        "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if w.dtype == "f16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}-shaped: batch {B}, {L} exit points "
+                               + ",".join(f"[{c},{h},{wd}]" for c, h, wd in w.exits)
+                               + f", {n} classes, hot {w.hot}, tau {w.tau}, tiers {w.tiers}, survivors gathered, "
+                                 "memory update every batch",
+                   "exits_per_exit_point": exits.mean(axis=0).round(1).tolist(),
+                   "ran_to_end": float(live[:, -1].mean())},
+        "roofline": {"bound": "hbm", "kernel": "k_encode_direct<f16,16B>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
+        "cpu_baseline": {"value": ns / cpu_s, "unit": "frames/s", "cores": cores, "kind": "oracle",
+                         "sample": f"first {ns} frames of the same batch, all {L} exit points and the memory "
+                                   f"update, {cpu_s:.2f} s"},
+        "encode_ms_per_exit_point": enc_ms.mean(axis=0).round(4).tolist(),
+        "encode_gbs_per_exit_point": (enc_bytes.mean(axis=0) / (enc_ms.mean(axis=0) * 1e-3) / 1e9).round(1).tolist(),
+        "path_hbm_frac": stage_gbs / HBM_PEAK_GBS,
+    }
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -53,6 +53,8 @@ struct smtm_ctx {
     uint32_t* cls_cnt;
     int32_t* cls_last;
     uint64_t* score;
+    uint64_t* score_total;                       // [2] 128-bit sum of the scores
+    int32_t* below;                              // [1] classes whose prefix share is below the confidence level
     int32_t* order;
     // pinned staging for small host -> device copies
     void* pinned;
@@ -198,6 +200,8 @@ int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
     CREATE_TRY(dev_alloc(ctx, &ctx->cls_last, (size_t)n));
     CREATE_TRY(dev_alloc(ctx, &ctx->score, (size_t)n));
     CREATE_TRY(dev_alloc(ctx, &ctx->order, (size_t)n));
+    CREATE_TRY(dev_alloc(ctx, &ctx->score_total, (size_t)2));
+    CREATE_TRY(dev_alloc(ctx, &ctx->below, (size_t)1));
     ctx->pinned_bytes = sizeof(int32_t) * (size_t)cfg->hot_max;
     CREATE_TRY(hipHostMalloc(&ctx->pinned, ctx->pinned_bytes, hipHostMallocDefault));
 
@@ -442,9 +446,7 @@ int32_t smtm_batch_results(smtm_ctx* ctx, int32_t* exit_layer, int32_t* label, i
     if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
     if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (exit_layer) launch_copy_i32(ctx->res_layer, exit_layer, ctx->batch, st);
-    if (label) launch_copy_i32(ctx->res_label, label, ctx->batch, st);
-    if (tier) launch_copy_i32(ctx->res_tier, tier, ctx->batch, st);
+    launch_copy3_i32(ctx->res_layer, exit_layer, ctx->res_label, label, ctx->res_tier, tier, ctx->batch, st);
     return check_launch(ctx, "smtm_batch_results");
 }
 
@@ -479,12 +481,22 @@ int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* st
     hipStream_t st = static_cast<hipStream_t>(stream);
     const smtm_config& c = ctx->cfg;
     const int n = c.n_classes;
-    launch_tables_update(label, batch, n, ctx->FT, ctx->TS, ctx->cls_cnt, ctx->cls_last, st);
-    for (int l = 0; l < c.n_exits; ++l)
-        launch_centres_update(ctx->centres[l], ctx->mcount[l], ctx->cinv[l], ctx->chat[l], ctx->Cp[l], ctx->sv[l],
-                              c.dims[l], n, l, label, stop_layer, batch, ctx->cls_cnt, st);
-    launch_policy(ctx->FT, ctx->TS, n, (uint32_t)c.window, (uint32_t)c.cl_num, (uint32_t)c.cl_den, c.hot_min,
-                  c.hot_max, ctx->score, ctx->order, ctx->hot_ids, ctx->in_hot, ctx->counts, st);
+    launch_tables_update(label, batch, n, (uint32_t)c.window, ctx->FT, ctx->TS, ctx->cls_cnt, ctx->cls_last,
+                         ctx->score, ctx->score_total, ctx->below, st);
+    CentreTables tabs;
+    for (int l = 0; l < SMTM_MAX_EXITS; ++l) {
+        const bool on = l < c.n_exits;
+        tabs.centres[l] = on ? ctx->centres[l] : nullptr;
+        tabs.mcount[l] = on ? ctx->mcount[l] : nullptr;
+        tabs.cinv[l] = on ? ctx->cinv[l] : nullptr;
+        tabs.chat[l] = on ? ctx->chat[l] : nullptr;
+        tabs.sv[l] = on ? ctx->sv[l] : nullptr;
+        tabs.C[l] = on ? c.dims[l] : 0;
+        tabs.Cp[l] = on ? ctx->Cp[l] : 0;
+    }
+    launch_centres_update(tabs, c.n_exits, n, label, stop_layer, batch, ctx->cls_cnt, st);
+    launch_policy(ctx->score, ctx->score_total, n, (uint32_t)c.cl_num, (uint32_t)c.cl_den, c.hot_min, c.hot_max,
+                  ctx->order, ctx->below, ctx->hot_ids, ctx->in_hot, ctx->counts, st);
     return check_launch(ctx, "smtm_cache_update");
 }
 

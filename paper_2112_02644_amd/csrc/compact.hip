@@ -128,9 +128,19 @@ __global__ __launch_bounds__(256) void k_gather_rows(const char* __restrict__ sr
         const int64_t row = row_ids ? row_ids[old_slot] : old_slot;
         const V* from = reinterpret_cast<const V*>(src + row * row_bytes);
         V* to = reinterpret_cast<V*>(dst + (int64_t)s * row_bytes);
-        for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < per_row;
-             q += (int64_t)gridDim.x * blockDim.x)
-            __builtin_nontemporal_store(__builtin_nontemporal_load(from + q), to + q);
+        const int64_t step = (int64_t)gridDim.x * blockDim.x;
+        int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        for (; q + 3 * step < per_row; q += 4 * step) {   // four loads in flight, then four stores
+            const V a = __builtin_nontemporal_load(from + q);
+            const V b = __builtin_nontemporal_load(from + q + step);
+            const V c = __builtin_nontemporal_load(from + q + 2 * step);
+            const V d = __builtin_nontemporal_load(from + q + 3 * step);
+            __builtin_nontemporal_store(a, to + q);
+            __builtin_nontemporal_store(b, to + q + step);
+            __builtin_nontemporal_store(c, to + q + 2 * step);
+            __builtin_nontemporal_store(d, to + q + 3 * step);
+        }
+        for (; q < per_row; q += step) __builtin_nontemporal_store(__builtin_nontemporal_load(from + q), to + q);
     }
 }
 
@@ -155,15 +165,23 @@ void launch_gather_rows(const void* src, const int32_t* row_ids, const int32_t* 
         hipLaunchKernelGGL((k_gather_rows<uint16_t>), grid, dim3(256), 0, st, s, row_ids, next_slots, counts, max_rows, d, row_bytes);
 }
 
-__global__ void k_copy_i32(const int32_t* __restrict__ src, int32_t* __restrict__ dst, int count) {
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += gridDim.x * blockDim.x) dst[i] = src[i];
+// Up to three int32 arrays copied in one launch (a NULL destination is skipped).
+__global__ void k_copy3_i32(const int32_t* __restrict__ s0, int32_t* __restrict__ d0,
+                            const int32_t* __restrict__ s1, int32_t* __restrict__ d1,
+                            const int32_t* __restrict__ s2, int32_t* __restrict__ d2, int count) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += gridDim.x * blockDim.x) {
+        if (d0) d0[i] = s0[i];
+        if (d1) d1[i] = s1[i];
+        if (d2) d2[i] = s2[i];
+    }
 }
 
-void launch_copy_i32(const int32_t* src, int32_t* dst, int count, hipStream_t st) {
-    if (count <= 0) return;
+void launch_copy3_i32(const int32_t* s0, int32_t* d0, const int32_t* s1, int32_t* d1, const int32_t* s2,
+                      int32_t* d2, int count, hipStream_t st) {
+    if (count <= 0 || (!d0 && !d1 && !d2)) return;
     int grid = (count + 255) / 256;
     if (grid > 256) grid = 256;
-    hipLaunchKernelGGL(k_copy_i32, dim3(grid), dim3(256), 0, st, src, dst, count);
+    hipLaunchKernelGGL(k_copy3_i32, dim3(grid), dim3(256), 0, st, s0, d0, s1, d1, s2, d2, count);
 }
 
 __global__ void k_fill_u32(uint32_t* __restrict__ dst, uint32_t value, int count) {

@@ -58,20 +58,29 @@ void launch_compact(const int32_t* decision, const int32_t* label, const int32_t
 void launch_gather_rows(const void* src, const int32_t* row_ids, const int32_t* next_slots,
                         const Counts* counts, int max_rows, void* dst, int64_t row_bytes,
                         hipStream_t st);
-void launch_copy_i32(const int32_t* src, int32_t* dst, int count, hipStream_t st);
+void launch_copy3_i32(const int32_t* s0, int32_t* d0, const int32_t* s1, int32_t* d1, const int32_t* s2,
+                      int32_t* d2, int count, hipStream_t st);
 void launch_set_hot(const int32_t* ids, int k, int n, int32_t* hot_ids, uint8_t* in_hot, Counts* counts,
                     hipStream_t st);
 void launch_fill_u32(uint32_t* dst, uint32_t value, int count, hipStream_t st);
 
 // ---- update.hip -------------------------------------------------------------------------
-void launch_tables_update(const int32_t* label, int batch, int n, uint32_t* FT, uint32_t* TS,
-                          uint32_t* cls_cnt, int32_t* cls_last, hipStream_t st);
-void launch_centres_update(float* centres, uint32_t* mcount, float* cinv, _Float16* chat, int Cp,
-                           const float* sv_by_frame, int C, int n, int exit_index /*0-based*/,
-                           const int32_t* label, const int32_t* stop_layer, int batch,
-                           const uint32_t* cls_cnt, hipStream_t st);
-void launch_policy(const uint32_t* FT, const uint32_t* TS, int n, uint32_t W, uint32_t cl_num,
-                   uint32_t cl_den, int hot_min, int hot_max, uint64_t* score, int32_t* order,
-                   int32_t* hot_ids, uint8_t* in_hot, Counts* counts, hipStream_t st);
+struct CentreTables {                     // per exit point, passed by value to the centre-update kernel
+    float* centres[SMTM_MAX_EXITS];
+    uint32_t* mcount[SMTM_MAX_EXITS];
+    float* cinv[SMTM_MAX_EXITS];
+    _Float16* chat[SMTM_MAX_EXITS];
+    const float* sv[SMTM_MAX_EXITS];
+    int C[SMTM_MAX_EXITS];
+    int Cp[SMTM_MAX_EXITS];
+};
+void launch_tables_update(const int32_t* label, int batch, int n, uint32_t W, uint32_t* FT, uint32_t* TS,
+                          uint32_t* cls_cnt, int32_t* cls_last, uint64_t* score, uint64_t* total,
+                          int32_t* below, hipStream_t st);
+void launch_centres_update(const CentreTables& tabs, int n_exits, int n, const int32_t* label,
+                           const int32_t* stop_layer, int batch, const uint32_t* cls_cnt, hipStream_t st);
+void launch_policy(const uint64_t* score, const uint64_t* total, int n, uint32_t cl_num, uint32_t cl_den,
+                   int hot_min, int hot_max, int32_t* order, int32_t* below, int32_t* hot_ids,
+                   uint8_t* in_hot, Counts* counts, hipStream_t st);
 
 }  // namespace smtm

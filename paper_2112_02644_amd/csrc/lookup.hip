@@ -58,7 +58,11 @@ void launch_centre_prepare(const float* centres, int n, int C, float* cinv, _Flo
                        chat, Cp, row_lo, row_hi);
 }
 
-// One wavefront per live slot: 1/|SV| and (optionally) the unit-normalised fp16 row for the MFMA path.
+// One wavefront per live slot: 1/|SV| and (optionally) the unit-normalised fp16 row for the MFMA
+// path.  The row is read with 16-byte loads, four per lane in flight, when C is a multiple of 4.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+
 __global__ __launch_bounds__(256) void k_rownorm(const float* __restrict__ sv,
                                                  const int32_t* __restrict__ frame_ids,
                                                  const Counts* __restrict__ counts, int max_rows, int C,
@@ -68,18 +72,47 @@ __global__ __launch_bounds__(256) void k_rownorm(const float* __restrict__ sv,
     int n_live = counts->n_live;
     if (n_live > max_rows) n_live = max_rows;
     const int n_waves = gridDim.x * 4;
+    const bool vec = (C & 3) == 0;
     for (int slot = blockIdx.x * 4 + (threadIdx.x >> 6); slot < n_live; slot += n_waves) {
         const float* p = sv + (int64_t)frame_ids[slot] * C;
         float ss = 0.f;
-        for (int c = lane; c < C; c += 64) { const float x = p[c]; ss += x * x; }
+        if (vec) {
+            const f32x4* p4 = reinterpret_cast<const f32x4*>(p);
+            const int nq = C >> 2;
+            for (int base = 0; base < nq; base += 256) {
+                f32x4 x[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = base + u * 64 + lane;
+                    x[u] = q < nq ? p4[q] : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    ss += (x[u].x * x[u].x + x[u].y * x[u].y) + (x[u].z * x[u].z + x[u].w * x[u].w);
+            }
+        } else {
+            for (int c = lane; c < C; c += 64) { const float x = p[c]; ss += x * x; }
+        }
         ss = wave_sum(ss);
         const float inv = inv_norm_of(ss);
         if (lane == 0) vinv[slot] = inv;
         if (vhat) {
-            for (int c = lane; c < Cp; c += 64) {
-                float x = 0.f;
-                if (c < C && inv != 0.f) x = p[c] * inv;
-                vhat[(int64_t)slot * Cp + c] = (_Float16)x;
+            _Float16* out = vhat + (int64_t)slot * Cp;
+            if (vec) {
+                const f32x4* p4 = reinterpret_cast<const f32x4*>(p);
+                const int nq = C >> 2, nqp = Cp >> 2;       // Cp is a multiple of 64
+                for (int q = lane; q < nqp; q += 64) {
+                    f32x4 x = {0.f, 0.f, 0.f, 0.f};
+                    if (q < nq && inv != 0.f) x = p4[q] * inv;
+                    half4_t h = {(_Float16)x.x, (_Float16)x.y, (_Float16)x.z, (_Float16)x.w};
+                    *reinterpret_cast<half4_t*>(out + 4 * q) = h;
+                }
+            } else {
+                for (int c = lane; c < Cp; c += 64) {
+                    float x = 0.f;
+                    if (c < C && inv != 0.f) x = p[c] * inv;
+                    out[c] = (_Float16)x;
+                }
             }
         }
     }
@@ -306,13 +339,41 @@ __global__ __launch_bounds__(256) void k_top2_decide(
     if (n_live > max_rows) n_live = max_rows;
     const int n_waves = gridDim.x * 4;
     const float ninf = -__builtin_inff();
+    const bool vec = (n & 3) == 0;
     for (int slot = blockIdx.x * 4 + (threadIdx.x >> 6); slot < n_live; slot += n_waves) {
         const float* row = SA + (int64_t)frame_ids[slot] * n;
         Top2 hot = {ninf, -1, ninf}, all = {ninf, -1, ninf};
-        for (int j = lane; j < n; j += 64) {
-            const float x = row[j];
-            top2_push(all, x, j);
-            if (in_hot[j]) top2_push(hot, x, j);
+        if (vec) {
+            // each lane takes 4 consecutive classes per access, four accesses in flight
+            const f32x4* row4 = reinterpret_cast<const f32x4*>(row);
+            const uint32_t* hot4 = reinterpret_cast<const uint32_t*>(in_hot);
+            const int nq = n >> 2;
+            for (int base = 0; base < nq; base += 256) {
+                f32x4 x[4];
+                uint32_t h[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = base + u * 64 + lane;
+                    if (q < nq) { x[u] = row4[q]; h[u] = hot4[q]; }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = base + u * 64 + lane;
+                    if (q < nq) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            top2_push(all, x[u][e], 4 * q + e);
+                            if ((h[u] >> (8 * e)) & 0xffu) top2_push(hot, x[u][e], 4 * q + e);
+                        }
+                    }
+                }
+            }
+        } else {
+            for (int j = lane; j < n; j += 64) {
+                const float x = row[j];
+                top2_push(all, x, j);
+                if (in_hot[j]) top2_push(hot, x, j);
+            }
         }
         for (int off = 32; off > 0; off >>= 1) {
             float v1 = __shfl_xor(all.v1, off, 64); int id1 = __shfl_xor(all.id1, off, 64);

@@ -1,24 +1,50 @@
 // Memory update between batches (arXiv 2112.02644, Sec. 6): frequency and time-stamp tables
 // (Sec. 6.1), replacement score (Eq. 5), adaptive fast-memory size (Eq. 6), adaptive centres
 // (Eq. 7).  Tables, scores, order and size are exact integer work; only the centres are
-// floating point.  All of it is a few thousand entries: latency-bound, one or a few blocks.
+// floating point.  All of it is a few thousand entries: latency-bound, so the work is spread
+// over many short lanes rather than a few long loops.
 #include "internal.h"
 
 namespace smtm {
 
 typedef unsigned __int128 u128;
 
+__device__ __forceinline__ uint64_t score_of(uint32_t ft, uint32_t ts, uint32_t W) {
+    // Eq. 5 scaled by 4^15: FT * 4^(15 - min(floor(TS / W), 15)), exact in 64 bits
+    uint32_t q = ts / W;
+    if (q > 15u) q = 15u;
+    return (uint64_t)ft << (2u * (15u - q));
+}
+
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t x, int off) {
+    uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
+    lo = __shfl_xor(lo, off, 64);
+    hi = __shfl_xor(hi, off, 64);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ u128 shfl_xor_u128(u128 x, int off) {
+    return ((u128)shfl_xor_u64((uint64_t)(x >> 64), off) << 64) | shfl_xor_u64((uint64_t)x, off);
+}
+
 // Frequency / time-stamp tables for a whole batch, equal to taking the frames one by one:
 // FT_j += (appearances of j);  TS_j = (frames after j's last appearance) if j appeared,
-// else TS_j + batch.  Both saturate at 2^32 - 1.  Single block.
+// else TS_j + batch.  Both saturate at 2^32 - 1.  Also leaves every class's score and the
+// 128-bit total of the scores (total[0] low, total[1] high) and clears the policy counter.
+// Single block of 1024 threads.
 __global__ __launch_bounds__(1024) void k_tables_update(const int32_t* __restrict__ label, int batch,
-                                                        int n, uint32_t* __restrict__ FT,
+                                                        int n, uint32_t W, uint32_t* __restrict__ FT,
                                                         uint32_t* __restrict__ TS,
                                                         uint32_t* __restrict__ cls_cnt,
-                                                        int32_t* __restrict__ cls_last) {
-    for (int i = threadIdx.x; i < n; i += blockDim.x) { cls_cnt[i] = 0; cls_last[i] = -1; }
+                                                        int32_t* __restrict__ cls_last,
+                                                        uint64_t* __restrict__ score,
+                                                        uint64_t* __restrict__ total,
+                                                        int32_t* __restrict__ below) {
+    __shared__ uint64_t red_lo[16], red_hi[16];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < n; i += 1024) { cls_cnt[i] = 0; cls_last[i] = -1; }
     __syncthreads();
-    for (int b = threadIdx.x; b < batch; b += blockDim.x) {
+    for (int b = tid; b < batch; b += 1024) {
         const int j = label[b];
         if (j >= 0 && j < n) {
             atomicAdd(&cls_cnt[j], 1u);
@@ -26,153 +52,175 @@ __global__ __launch_bounds__(1024) void k_tables_update(const int32_t* __restric
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-        const uint64_t ft = (uint64_t)FT[i] + cls_cnt[i];
-        FT[i] = ft > 0xffffffffull ? 0xffffffffu : (uint32_t)ft;
+    u128 part = 0;
+    for (int i = tid; i < n; i += 1024) {
+        uint64_t ft = (uint64_t)FT[i] + cls_cnt[i];
+        if (ft > 0xffffffffull) ft = 0xffffffffull;
         uint64_t ts;
         if (cls_last[i] >= 0) ts = (uint64_t)(batch - 1 - cls_last[i]);
         else ts = (uint64_t)TS[i] + (uint64_t)batch;
-        TS[i] = ts > 0xffffffffull ? 0xffffffffu : (uint32_t)ts;
+        if (ts > 0xffffffffull) ts = 0xffffffffull;
+        FT[i] = (uint32_t)ft;
+        TS[i] = (uint32_t)ts;
+        const uint64_t s = score_of((uint32_t)ft, (uint32_t)ts, W);
+        score[i] = s;
+        part += s;
     }
-}
-
-void launch_tables_update(const int32_t* label, int batch, int n, uint32_t* FT, uint32_t* TS,
-                          uint32_t* cls_cnt, int32_t* cls_last, hipStream_t st) {
-    hipLaunchKernelGGL(k_tables_update, dim3(1), dim3(1024), 0, st, label, batch, n, FT, TS, cls_cnt,
-                       cls_last);
-}
-
-// Adaptive centres (Eq. 7) for one exit point.  Taking the frames of class j one by one gives
-// the running mean (m*SC + sum of their SV) / (m + count); the sum is taken in ascending frame
-// order so the result does not depend on scheduling.  One block per class that appeared; the
-// block also refreshes 1/|SC_j| and the unit fp16 copy.
-__global__ __launch_bounds__(256) void k_centres_update(
-    float* __restrict__ centres, uint32_t* __restrict__ mcount, float* __restrict__ cinv,
-    _Float16* __restrict__ chat, int Cp, const float* __restrict__ sv, int C, int n, int exit_index,
-    const int32_t* __restrict__ label, const int32_t* __restrict__ stop_layer, int batch,
-    const uint32_t* __restrict__ cls_cnt) {
-    __shared__ float red[4];
-    __shared__ int s_cnt;
-    const int j = blockIdx.x;
-    if (j >= n || cls_cnt[j] == 0) return;               // uniform over the block
-    const int tid = threadIdx.x;
-    float* sc = centres + (int64_t)j * C;
-    const float m = (float)mcount[j];
-    // count the frames that update this exit point (label == j and stopped at or after it)
-    int cnt = 0;
-    float ss = 0.f;
-    for (int c0 = 0; c0 < C; c0 += 256) {                // uniform trip count
-        const int c = c0 + tid;
-        float sum = 0.f;
-        cnt = 0;
-        for (int b = 0; b < batch; ++b) {
-            if (label[b] == j && stop_layer[b] > exit_index) {
-                ++cnt;
-                if (c < C) sum += sv[(int64_t)b * C + c];
-            }
-        }
-        if (c < C && cnt > 0) {
-            const float x = (sc[c] * m + sum) / (m + (float)cnt);
-            sc[c] = x;
-            ss += x * x;
-        } else if (c < C) {
-            const float x = sc[c];
-            ss += x * x;
-        }
-    }
-    if (tid == 0) s_cnt = cnt;
-    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    for (int off = 32; off > 0; off >>= 1) part += shfl_xor_u128(part, off);
+    if ((tid & 63) == 0) { red_lo[tid >> 6] = (uint64_t)part; red_hi[tid >> 6] = (uint64_t)(part >> 64); }
     __syncthreads();
-    if (s_cnt == 0) return;                              // uniform: nothing changed at this exit point
+    if (tid == 0) {
+        u128 t = 0;
+        for (int w = 0; w < 16; ++w) t += ((u128)red_hi[w] << 64) | red_lo[w];
+        total[0] = (uint64_t)t; total[1] = (uint64_t)(t >> 64);
+        *below = 0;
+    }
+}
+
+void launch_tables_update(const int32_t* label, int batch, int n, uint32_t W, uint32_t* FT, uint32_t* TS,
+                          uint32_t* cls_cnt, int32_t* cls_last, uint64_t* score, uint64_t* total,
+                          int32_t* below, hipStream_t st) {
+    hipLaunchKernelGGL(k_tables_update, dim3(1), dim3(1024), 0, st, label, batch, n, W, FT, TS, cls_cnt,
+                       cls_last, score, total, below);
+}
+
+// Adaptive centres (Eq. 7), all exit points in one launch: block (j, l0) handles class j at
+// exit point l0.  Taking the frames of class j one by one gives the running mean
+// (m*SC + sum of their SV) / (m + count); the sum is taken in ascending frame order, so the
+// result does not depend on scheduling.  The block lists the frames that update it (label == j
+// and stopped at or after this exit point) with a ballot/prefix pass over the labels, then
+// each thread adds up its channels over that list.  It also refreshes 1/|SC_j| and the unit
+// fp16 copy of the row.
+constexpr int kListCap = 4096;
+
+__global__ __launch_bounds__(256) void k_centres_update(CentreTables tabs, int n, const int32_t* __restrict__ label,
+                                                        const int32_t* __restrict__ stop_layer, int batch,
+                                                        const uint32_t* __restrict__ cls_cnt) {
+    __shared__ int list[kListCap];
+    __shared__ int w_cnt[4];
+    __shared__ float red[4];
+    const int j = blockIdx.x, l0 = blockIdx.y;
+    if (cls_cnt[j] == 0) return;                         // uniform over the block
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int C = tabs.C[l0], Cp = tabs.Cp[l0];
+    float* sc = tabs.centres[l0] + (int64_t)j * C;
+    const float* sv = tabs.sv[l0];
+
+    // frames of this class that reached this exit point, ascending
+    int cnt = 0;
+    bool overflow = false;
+    for (int b0 = 0; b0 < batch; b0 += 256) {            // uniform trip count
+        const int b = b0 + tid;
+        const bool hit = b < batch && label[b] == j && stop_layer[b] > l0;
+        const unsigned long long m = __ballot(hit);
+        if (lane == 0) w_cnt[wave] = __popcll(m);
+        __syncthreads();
+        int off = 0, tot = 0;
+        for (int w = 0; w < 4; ++w) { if (w < wave) off += w_cnt[w]; tot += w_cnt[w]; }
+        if (hit) {
+            const int pos = cnt + off + __popcll(m & ((1ull << lane) - 1ull));
+            if (pos < kListCap) list[pos] = b;
+        }
+        cnt += tot;
+        __syncthreads();
+    }
+    if (cnt == 0) return;                                // uniform: nothing to do at this exit point
+    overflow = cnt > kListCap;
+    const float m_old = (float)tabs.mcount[l0][j];
+    float ss = 0.f;
+    for (int c = tid; c < C; c += 256) {
+        float sum = 0.f;
+        if (!overflow) {
+            int i = 0;
+            for (; i + 4 <= cnt; i += 4) {               // four independent loads in flight
+                const float a0 = sv[(int64_t)list[i] * C + c], a1 = sv[(int64_t)list[i + 1] * C + c];
+                const float a2 = sv[(int64_t)list[i + 2] * C + c], a3 = sv[(int64_t)list[i + 3] * C + c];
+                sum += a0; sum += a1; sum += a2; sum += a3;
+            }
+            for (; i < cnt; ++i) sum += sv[(int64_t)list[i] * C + c];
+        } else {                                         // more frames of one class than the list holds
+            for (int b = 0; b < batch; ++b)
+                if (label[b] == j && stop_layer[b] > l0) sum += sv[(int64_t)b * C + c];
+        }
+        const float x = (sc[c] * m_old + sum) / (m_old + (float)cnt);
+        sc[c] = x;
+        ss += x * x;
+    }
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if (lane == 0) red[wave] = ss;
+    __syncthreads();
     const float nrm2 = (red[0] + red[1]) + (red[2] + red[3]);
     float inv = 0.f;
     if (nrm2 > 0.f && nrm2 < __builtin_inff()) inv = 1.0f / sqrtf(nrm2);
     if (tid == 0) {
-        cinv[j] = inv;
-        const uint64_t mm = (uint64_t)mcount[j] + (uint64_t)s_cnt;
-        mcount[j] = mm > 0xffffffffull ? 0xffffffffu : (uint32_t)mm;
+        tabs.cinv[l0][j] = inv;
+        const uint64_t mm = (uint64_t)tabs.mcount[l0][j] + (uint64_t)cnt;
+        tabs.mcount[l0][j] = mm > 0xffffffffull ? 0xffffffffu : (uint32_t)mm;
     }
+    _Float16* ch = tabs.chat[l0] + (int64_t)j * Cp;
     for (int c = tid; c < Cp; c += 256) {
         float x = 0.f;
-        if (c < C && inv != 0.f) x = sc[c] * inv;       // sc[c] was written by this same thread (c % 256 == tid)
-        chat[(int64_t)j * Cp + c] = (_Float16)x;
+        if (c < C && inv != 0.f) x = sc[c] * inv;        // sc[c] was written by this same thread
+        ch[c] = (_Float16)x;
     }
 }
 
-void launch_centres_update(float* centres, uint32_t* mcount, float* cinv, _Float16* chat, int Cp,
-                           const float* sv, int C, int n, int exit_index, const int32_t* label,
-                           const int32_t* stop_layer, int batch, const uint32_t* cls_cnt,
-                           hipStream_t st) {
-    hipLaunchKernelGGL(k_centres_update, dim3(n), dim3(256), 0, st, centres, mcount, cinv, chat, Cp, sv, C,
-                       n, exit_index, label, stop_layer, batch, cls_cnt);
+void launch_centres_update(const CentreTables& tabs, int n_exits, int n, const int32_t* label,
+                           const int32_t* stop_layer, int batch, const uint32_t* cls_cnt, hipStream_t st) {
+    hipLaunchKernelGGL(k_centres_update, dim3(n, n_exits), dim3(256), 0, st, tabs, n, label, stop_layer,
+                       batch, cls_cnt);
 }
 
-// Replacement policy and adaptive size.  Single block of 1024 threads.
-//   score_i = FT_i * 4^(15 - min(floor(TS_i / W), 15))       (Eq. 5 scaled by 4^15, exact)
+// Replacement policy and adaptive size (Eq. 5, Eq. 6), two launches.
 //   rank_i  = number of classes ahead of i in (score desc, id asc) order
-//   k       = 1 + number of ranks whose inclusive prefix sum is still below CL * total
-//             (the prefix share is non-decreasing in the rank), clamped to [hot_min, hot_max]
-__device__ __forceinline__ uint64_t score_of(uint32_t ft, uint32_t ts, uint32_t W) {
-    uint32_t q = ts / W;
-    if (q > 15u) q = 15u;
-    return (uint64_t)ft << (2u * (15u - q));
-}
-
-__global__ __launch_bounds__(1024) void k_policy(const uint32_t* __restrict__ FT,
-                                                 const uint32_t* __restrict__ TS, int n, uint32_t W,
-                                                 uint32_t cl_num, uint32_t cl_den, int hot_min,
-                                                 int hot_max, uint64_t* __restrict__ score,
-                                                 int32_t* __restrict__ order,
-                                                 int32_t* __restrict__ hot_ids,
-                                                 uint8_t* __restrict__ in_hot,
-                                                 Counts* __restrict__ counts) {
-    __shared__ uint64_t red_lo[1024], red_hi[1024];
-    __shared__ int red_cnt[1024];
-    const int tid = threadIdx.x;
-    u128 part = 0;
-    for (int i = tid; i < n; i += 1024) {
-        const uint64_t s = score_of(FT[i], TS[i], W);
-        score[i] = s;
-        part += s;
-    }
-    red_lo[tid] = (uint64_t)part; red_hi[tid] = (uint64_t)(part >> 64);
-    __syncthreads();
-    for (int off = 512; off > 0; off >>= 1) {
-        if (tid < off) {
-            u128 a = ((u128)red_hi[tid] << 64) | red_lo[tid];
-            u128 b = ((u128)red_hi[tid + off] << 64) | red_lo[tid + off];
-            a += b;
-            red_lo[tid] = (uint64_t)a; red_hi[tid] = (uint64_t)(a >> 64);
-        }
-        __syncthreads();
-    }
-    const u128 total = ((u128)red_hi[0] << 64) | red_lo[0];
-    if (total == 0) return;                              // no history: the fast memory stays as it is
-    const u128 need = total * cl_num;                    // prefix * cl_den >= total * cl_num
-    int below = 0;
-    for (int i = tid; i < n; i += 1024) {
-        const uint64_t si = score[i];
-        int rank = 0;
-        u128 prefix = si;                                // inclusive prefix sum at i's rank
-        for (int j = 0; j < n; ++j) {
+//   prefix_i = sum of the scores of the classes up to and including i in that order
+//   k       = 1 + number of classes whose prefix is still below CL * total
+//             (the prefix share is non-decreasing along the order), clamped to [hot_min, hot_max]
+// k_policy_rank: 16 lanes per class split the scan over all classes and combine with shuffles.
+__global__ __launch_bounds__(256) void k_policy_rank(const uint64_t* __restrict__ score,
+                                                     const uint64_t* __restrict__ total, int n,
+                                                     uint32_t cl_num, uint32_t cl_den,
+                                                     int32_t* __restrict__ order,
+                                                     int32_t* __restrict__ below) {
+    const int tid = threadIdx.x, sub = tid & 15;
+    const int i = blockIdx.x * 16 + (tid >> 4);
+    const u128 tot = ((u128)total[1] << 64) | total[0];
+    if (tot == 0) return;                                // no history: nothing changes (uniform)
+    const bool valid = i < n;
+    const uint64_t si = valid ? score[i] : 0;
+    int rank = 0;
+    u128 prefix = 0;
+    if (valid) {
+        for (int j = sub; j < n; j += 16) {
             const uint64_t sj = score[j];
             if (sj > si || (sj == si && j < i)) { ++rank; prefix += sj; }
         }
+    }
+    for (int off = 8; off > 0; off >>= 1) {
+        rank += __shfl_xor(rank, off, 64);
+        prefix += shfl_xor_u128(prefix, off);
+    }
+    if (valid && sub == 0) {
+        prefix += si;
         order[rank] = i;
-        if (prefix * cl_den < need) ++below;
+        if (prefix * cl_den < tot * cl_num) atomicAdd(below, 1);
     }
-    red_cnt[tid] = below;
-    __syncthreads();
-    for (int off = 512; off > 0; off >>= 1) {
-        if (tid < off) red_cnt[tid] += red_cnt[tid + off];
-        __syncthreads();
-    }
-    int k = red_cnt[0] + 1;
+}
+
+__global__ __launch_bounds__(1024) void k_policy_finish(const uint64_t* __restrict__ total, int n,
+                                                        int hot_min, int hot_max,
+                                                        const int32_t* __restrict__ order,
+                                                        const int32_t* __restrict__ below,
+                                                        int32_t* __restrict__ hot_ids,
+                                                        uint8_t* __restrict__ in_hot,
+                                                        Counts* __restrict__ counts) {
+    if ((total[0] | total[1]) == 0) return;              // no history: the fast memory stays as it is
+    const int tid = threadIdx.x;
+    int k = *below + 1;
     if (k < hot_min) k = hot_min;
     if (k > hot_max) k = hot_max;
     for (int i = tid; i < n; i += 1024) in_hot[i] = 0;
-    __syncthreads();                                     // order[] and in_hot[] writes of this block are visible
+    __syncthreads();
     for (int r = tid; r < k; r += 1024) {
         const int id = order[r];
         hot_ids[r] = id;
@@ -181,11 +229,13 @@ __global__ __launch_bounds__(1024) void k_policy(const uint32_t* __restrict__ FT
     if (tid == 0) counts->hot_k = k;
 }
 
-void launch_policy(const uint32_t* FT, const uint32_t* TS, int n, uint32_t W, uint32_t cl_num,
-                   uint32_t cl_den, int hot_min, int hot_max, uint64_t* score, int32_t* order,
-                   int32_t* hot_ids, uint8_t* in_hot, Counts* counts, hipStream_t st) {
-    hipLaunchKernelGGL(k_policy, dim3(1), dim3(1024), 0, st, FT, TS, n, W, cl_num, cl_den, hot_min,
-                       hot_max, score, order, hot_ids, in_hot, counts);
+void launch_policy(const uint64_t* score, const uint64_t* total, int n, uint32_t cl_num, uint32_t cl_den,
+                   int hot_min, int hot_max, int32_t* order, int32_t* below, int32_t* hot_ids,
+                   uint8_t* in_hot, Counts* counts, hipStream_t st) {
+    hipLaunchKernelGGL(k_policy_rank, dim3((n + 15) / 16), dim3(256), 0, st, score, total, n, cl_num, cl_den,
+                       order, below);
+    hipLaunchKernelGGL(k_policy_finish, dim3(1), dim3(1024), 0, st, total, n, hot_min, hot_max, order, below,
+                       hot_ids, in_hot, counts);
 }
 
 }  // namespace smtm
