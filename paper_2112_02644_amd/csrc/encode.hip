@@ -6,6 +6,9 @@
 //   direct  a group of g lanes (g = 1..64, a power of two) owns one channel and walks it with
 //           VB-byte loads, up to UNR loads in flight per lane; 64/g channels per wavefront.
 //           Used when a channel's H*W*elem bytes are a multiple of VB.
+//   pair    when a channel is a multiple of 8 but not of 16 bytes (14x14 fp16 = 392 B), two
+//           neighbouring channels together are a multiple of 16: a lane group walks the pair
+//           with 16-byte loads and splits the one chunk that straddles the two channels.
 //   lds     for short, oddly sized channels (e.g. 7x7 fp16 = 98 B): a wavefront streams 64
 //           consecutive channels (one contiguous piece of the frame) with 16-byte loads into
 //           its own LDS region, then lane c adds up channel c from LDS.
@@ -33,6 +36,17 @@ template <> struct Chunk<_Float16, 16> {
         return (sum_halves(v.x) + sum_halves(v.y)) + (sum_halves(v.z) + sum_halves(v.w));
     }
 };
+template <typename T> struct Halves;          // sums of the lower and upper 8 bytes of a 16-byte chunk
+template <> struct Halves<_Float16> {
+    static __device__ __forceinline__ float lo(u32x4 v) { return sum_halves(v.x) + sum_halves(v.y); }
+    static __device__ __forceinline__ float hi(u32x4 v) { return sum_halves(v.z) + sum_halves(v.w); }
+};
+template <> struct Halves<float> {
+    // the whole vector is reinterpreted at once (a bit cast of a single vector element is not used here)
+    static __device__ __forceinline__ float lo(u32x4 v) { const f32x4 f = __builtin_bit_cast(f32x4, v); return f.x + f.y; }
+    static __device__ __forceinline__ float hi(u32x4 v) { const f32x4 f = __builtin_bit_cast(f32x4, v); return f.z + f.w; }
+};
+
 template <> struct Chunk<_Float16, 8> {
     typedef u32x2 V;
     static __device__ __forceinline__ float sum(V v) { return sum_halves(v.x) + sum_halves(v.y); }
@@ -76,8 +90,6 @@ __global__ __launch_bounds__(256) void k_encode_direct(
     int n_live = counts->n_live;
     if (n_live > max_rows) n_live = max_rows;
     const int64_t total = (int64_t)n_live * tpf;
-    const float inv_hw = 1.0f / (float)HW;
-    (void)inv_hw;
 
     for (int64_t t = wave; t < total; t += n_waves) {
         const int slot = (int)(t / tpf);
@@ -111,6 +123,72 @@ __global__ __launch_bounds__(256) void k_encode_direct(
             const float m = acc / (float)HW;
             sv[(int64_t)frame_ids[slot] * C + c] = m;
             if (sv_out) sv_out[(int64_t)slot * C + c] = m;
+        }
+    }
+}
+
+
+// pair path: channels 2p and 2p+1 of a frame form one run of nv2 = 2*H*W*sizeof(T)/16 chunks
+// (nv2 is odd); chunks below the middle one belong to channel 2p, those above to 2p+1, and the
+// middle chunk holds the last 8 bytes of the first and the first 8 bytes of the second.
+template <typename T, int UNR>
+__global__ __launch_bounds__(256) void k_encode_pair(
+    const T* __restrict__ F, const int32_t* __restrict__ row_ids,
+    const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows,
+    float* __restrict__ sv, float* __restrict__ sv_out, int C, int HW, int g_log2) {
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int n_waves = gridDim.x * (blockDim.x >> 6);
+    const int g = 1 << g_log2;
+    const int sub = lane & (g - 1);
+    const int grp = lane >> g_log2;
+    const int ppw = 64 >> g_log2;                       // channel pairs per wavefront task
+    const int n_pairs = C >> 1;                         // C is even on this path
+    const int tpf = (n_pairs + ppw - 1) / ppw;
+    const int nv2 = (int)((int64_t)HW * sizeof(T) / 8); // 16-byte chunks per pair (odd)
+    const int mid = nv2 >> 1;
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    const int64_t total = (int64_t)n_live * tpf;
+
+    for (int64_t t = wave; t < total; t += n_waves) {
+        const int slot = (int)(t / tpf);
+        const int pr = (int)(t - (int64_t)slot * tpf) * ppw + grp;
+        const int64_t row = row_ids ? row_ids[slot] : slot;
+        float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
+        if (pr < n_pairs) {
+            const char* p = reinterpret_cast<const char*>(F) + ((row * C + 2 * pr) * (int64_t)HW) * sizeof(T);
+            for (int base = 0; base < nv2; base += UNR << g_log2) {
+                u32x4 v[UNR];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    const int idx = base + (u << g_log2) + sub;
+                    if (idx < nv2)
+                        v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + (int64_t)idx * 16));
+                    else
+                        v[u] = u32x4{0u, 0u, 0u, 0u};
+                }
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    const int idx = base + (u << g_log2) + sub;
+                    const float lo = Halves<T>::lo(v[u]), hi = Halves<T>::hi(v[u]);
+                    // out-of-range chunks were loaded as zeros, so any side may take them
+                    const float to_a = idx < mid ? lo + hi : (idx == mid ? lo : 0.f);
+                    const float to_b = idx > mid ? lo + hi : (idx == mid ? hi : 0.f);
+                    if (u & 1) { a1 += to_a; b1 += to_b; } else { a0 += to_a; b0 += to_b; }
+                }
+            }
+        }
+        float a = a0 + a1, b = b0 + b1;
+        for (int off = g >> 1; off > 0; off >>= 1) {
+            a += __shfl_xor(a, off, 64);
+            b += __shfl_xor(b, off, 64);
+        }
+        if (sub == 0 && pr < n_pairs) {
+            const float ma = a / (float)HW, mb = b / (float)HW;
+            float* o = sv + (int64_t)frame_ids[slot] * C + 2 * pr;
+            o[0] = ma; o[1] = mb;
+            if (sv_out) { float* q = sv_out + (int64_t)slot * C + 2 * pr; q[0] = ma; q[1] = mb; }
         }
     }
 }
@@ -184,7 +262,7 @@ __global__ __launch_bounds__(256) void k_encode_lds(
 static int encode_grid(int64_t tasks_upper, int waves_per_block) {
     // enough resident wavefronts to cover HBM latency on 256 CUs, and no more blocks than tasks
     int64_t blocks = (tasks_upper + waves_per_block - 1) / waves_per_block;
-    const int64_t cap = 256 * 8;
+    const int64_t cap = 256 * 64;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     return (int)blocks;
@@ -206,6 +284,20 @@ static void launch_direct(const void* fmap, int C, int HW, const int32_t* row_id
                        C, HW, g_log2);
 }
 
+template <typename T>
+static void launch_pair(const void* fmap, int C, int HW, const int32_t* row_ids, const int32_t* frame_ids,
+                        const Counts* counts, int max_rows, float* sv, float* sv_out, hipStream_t st) {
+    constexpr int UNR = 8;
+    const int nv2 = (int)((int64_t)HW * sizeof(T) / 8);
+    int g_log2 = 0;
+    while (g_log2 < 6 && (nv2 + (1 << g_log2) - 1) / (1 << g_log2) > UNR) ++g_log2;
+    const int ppw = 64 >> g_log2;
+    const int64_t tasks = (int64_t)max_rows * ((C / 2 + ppw - 1) / ppw);
+    const int grid = encode_grid(tasks, 4);
+    hipLaunchKernelGGL((k_encode_pair<T, UNR>), dim3(grid), dim3(256), 0, st, static_cast<const T*>(fmap),
+                       row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW, g_log2);
+}
+
 const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
                           const int32_t* frame_ids, const Counts* counts, int max_rows,
                           float* sv, float* sv_out, hipStream_t st) {
@@ -217,6 +309,11 @@ const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int3
         else launch_direct<float, 16>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
         return "d16";
     }
+    if (ch_bytes % 8 == 0 && (C & 1) == 0) {
+        if (dtype == SMTM_F16) launch_pair<_Float16>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        else launch_pair<float>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        return "pair";
+    }
     if (ch_bytes % 8 == 0) {
         if (dtype == SMTM_F16) launch_direct<_Float16, 8>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
         else launch_direct<float, 8>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
@@ -225,7 +322,8 @@ const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int3
     if (frame_bytes % 16 == 0 && ch_bytes <= 256) {
         const int tile_bytes = 64 * (int)ch_bytes;                 // multiple of 16 since 64*esz is
         const int gpf = (C + 63) / 64, bpf = (gpf + 3) / 4;
-        const int grid = encode_grid((int64_t)max_rows * bpf, 1);
+        int grid = encode_grid((int64_t)max_rows * bpf, 1);
+        if (grid > 256 * 8) grid = 256 * 8;
         const size_t lds = (size_t)tile_bytes * 4;
         if (dtype == SMTM_F16)
             hipLaunchKernelGGL((k_encode_lds<_Float16, 8>), dim3(grid), dim3(256), lds, st,

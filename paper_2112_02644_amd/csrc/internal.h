@@ -26,7 +26,7 @@ constexpr int kRowPad = 128;              // fp16 operand matrices are padded to
 static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // ---- encode.hip -------------------------------------------------------------------------
-// Picks the streaming path from the shape; returns a short name of the path ("d16", "d8", "lds", "d4", "d2").
+// Picks the streaming path from the shape; returns a short name of the path ("d16", "pair", "d8", "lds", "d4", "d2").
 const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
                           const int32_t* frame_ids, const Counts* counts, int max_rows,
                           float* sv_by_frame, float* sv_out_by_slot, hipStream_t st);

@@ -41,7 +41,10 @@ ENCODE_SHAPES = [
     # (dtype, rows, C, H, W)  -> path
     (torch.float16, 5, 7, 56, 56),     # d16, g = 64, ragged last iteration
     (torch.float16, 3, 9, 28, 28),     # d16, g = 16, C not a multiple of the 4 channels per wavefront
-    (torch.float16, 6, 13, 14, 14),    # d8
+    (torch.float16, 6, 13, 14, 14),    # d8 (odd channel count)
+    (torch.float16, 5, 10, 14, 14),    # pair: 392-byte channels walked two at a time with 16-byte loads
+    (torch.float16, 3, 130, 14, 14),   # pair, more pairs than one wavefront task holds
+    (torch.float32, 3, 6, 3, 2),       # pair fp32: 24-byte channels, three chunks per pair
     (torch.float16, 4, 136, 7, 7),     # lds, 2 full groups + tail of 8 channels (784 B)
     (torch.float16, 4, 24, 7, 7),      # lds, single short group
     (torch.float16, 3, 3, 7, 7),       # frame bytes not a multiple of 16 -> d2
