@@ -82,9 +82,8 @@ def main() -> int:
                 b.record()
             else:
                 ctx.encode(l, F, row_ids=ids)
-            ctx.lookup(l)
-            ctx.exit_compact(l, n_live_dev=live_ptr0 + 4 * (s * L + l - 1), fmap_in=F, row_ids=ids,
-                             fmap_out=gathers[l - 1], row_bytes=F[0].numel() * esz)
+            ctx.lookup_exit(l, n_live_dev=live_ptr0 + 4 * (s * L + l - 1), fmap_in=F, row_ids=ids,
+                            fmap_out=gathers[l - 1], row_bytes=F[0].numel() * esz)
         ctx.batch_results(res_layer, res_label, res_tier)
         ctx.cache_update(res_label, res_layer, B)
 
@@ -150,6 +149,9 @@ def main() -> int:
         "encode_gbs_per_exit_point": [None if np.isnan(t) else round(float(b / (t * 1e-3) / 1e9), 1)
                                       for b, t in zip(enc_bytes.mean(axis=0), enc_ms.mean(axis=0))],
         "path_hbm_frac": stage_gbs / HBM_PEAK_GBS,
+        # survivors after each exit point for every step run (warm-up included), so that per-dispatch
+        # byte counts of a profile of this command can be reconstructed
+        "survivors_log": live_log.cpu().numpy().tolist(),
     }
     print(json.dumps(out))
     ctx.close()

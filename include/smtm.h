@@ -155,6 +155,14 @@ int32_t smtm_exit_compact(smtm_ctx* ctx, int32_t exit,
                           const void* fmap_in, const int32_t* row_ids, void* fmap_out,
                           int64_t row_bytes, void* stream);
 
+/* 2 + 3 in one call, same results.  Arguments as in smtm_lookup (without sims_out) and
+ * smtm_exit_compact.  Requires smtm_encode for this exit point (else SMTM_ERR_STATE). */
+int32_t smtm_lookup_exit(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id,
+                         int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
+                         int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev,
+                         const void* fmap_in, const int32_t* row_ids, void* fmap_out,
+                         int64_t row_bytes, void* stream);
+
 /* 1 + 2 + 3 for one exit point, same results. */
 int32_t smtm_stage(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype,
                    int32_t H, int32_t W, const int32_t* row_ids,

@@ -218,6 +218,11 @@ int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
     CREATE_TRY(hipMemset(ctx->counts, 0, sizeof(Counts)));
     CREATE_TRY(hipMemset(ctx->vhat, 0, sizeof(_Float16) * (size_t)ctx->rows_pad * ctx->Cp_max));
     CREATE_TRY(hipMemset(ctx->SA, 0, sizeof(float) * (size_t)B * n));
+    CREATE_TRY(hipMemset(ctx->live[0], 0, sizeof(int32_t) * (size_t)B));
+    CREATE_TRY(hipMemset(ctx->live[1], 0, sizeof(int32_t) * (size_t)B));
+    CREATE_TRY(hipMemset(ctx->next_slots, 0, sizeof(int32_t) * (size_t)B));
+    CREATE_TRY(hipMemset(ctx->decision, 0, sizeof(int32_t) * (size_t)B));
+    CREATE_TRY(hipMemset(ctx->dlabel, 0, sizeof(int32_t) * (size_t)B));
     {
         int32_t* ids = static_cast<int32_t*>(ctx->pinned);
         for (int i = 0; i < cfg->hot_init; ++i) ids[i] = i;
@@ -358,13 +363,49 @@ int32_t smtm_encode(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype
     return SMTM_OK;
 }
 
-int32_t smtm_lookup(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id, float* sims_out, void* stream) {
+// --- lookup and exit/compact share these helpers ------------------------------------------
+
+static int32_t check_lookup_state(smtm_ctx* ctx, int32_t exit, const char* who) {
     int32_t rc = check_ctx_exit(ctx, exit);
     if (rc) return rc;
+    if (ctx->batch == 0 || ctx->stage_done[exit - 1] != 1)
+        return fail(ctx, SMTM_ERR_STATE, "%s(%d) needs smtm_encode(%d) first, once per batch", who, exit, exit);
+    return SMTM_OK;
+}
+
+static int32_t check_compact_args(smtm_ctx* ctx, const int32_t* live_ids, const void* fmap_in,
+                                  const int32_t* row_ids, const void* fmap_out, int64_t row_bytes) {
+    if ((fmap_in != nullptr) != (fmap_out != nullptr))
+        return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_in and fmap_out must be given together");
+    if (fmap_out) {
+        if (row_bytes < 2 || (row_bytes & 1)) return fail(ctx, SMTM_ERR_SHAPE, "row_bytes %lld must be even and >= 2", (long long)row_bytes);
+        if (((reinterpret_cast<uintptr_t>(fmap_in) | reinterpret_cast<uintptr_t>(fmap_out)) & 15u) != 0)
+            return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_in and fmap_out must be 16-byte aligned");
+        if (fmap_in == fmap_out) return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_out must not overlap fmap_in");
+    }
+    const int32_t* cur = ctx->live[ctx->cur];
+    const int32_t* nxt = ctx->live[ctx->cur ^ 1];
+    if (live_ids == cur || live_ids == nxt || row_ids == nxt)
+        return fail(ctx, SMTM_ERR_INVALID_ARG, "live_ids / row_ids alias the context's next live list");
+    return SMTM_OK;
+}
+
+static CompactArgs compact_args(smtm_ctx* ctx, int32_t exit, int32_t* exit_ids, int32_t* exit_labels,
+                                int32_t* exit_tier, int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev) {
+    CompactArgs a;
+    a.decision = ctx->decision; a.label = ctx->dlabel; a.frame_ids = ctx->live[ctx->cur];
+    a.next_ids = ctx->live[ctx->cur ^ 1]; a.next_slots = ctx->next_slots; a.counts = ctx->counts;
+    a.exit_index = exit;
+    a.exit_ids = exit_ids; a.exit_labels = exit_labels; a.exit_tier = exit_tier; a.n_exit_dev = n_exit_dev;
+    a.live_ids_user = live_ids; a.n_live_dev = n_live_dev;
+    a.res_layer = ctx->res_layer; a.res_label = ctx->res_label; a.res_tier = ctx->res_tier;
+    return a;
+}
+
+// scores, SA accumulation, top-2 and decisions
+static void enqueue_lookup(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id, float* sims_out,
+                           hipStream_t st) {
     const int l = exit - 1;
-    if (ctx->batch == 0 || ctx->stage_done[l] != 1)
-        return fail(ctx, SMTM_ERR_STATE, "smtm_lookup(%d) needs smtm_encode(%d) first, once per batch", exit, exit);
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const int n = ctx->cfg.n_classes, C = ctx->cfg.dims[l], B = ctx->batch;
     const int32_t* live = ctx->live[ctx->cur];
     int path = ctx->cfg.score_path;
@@ -380,9 +421,15 @@ int32_t smtm_lookup(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id
     }
     launch_top2_decide(ctx->SA, live, ctx->counts, B, n, ctx->in_hot, ctx->cfg.tiers, ctx->cfg.tau, ctx->decision,
                        ctx->dlabel, ctx->top_val, ctx->top_id, top_val, top_id, st);
+}
+
+int32_t smtm_lookup(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id, float* sims_out, void* stream) {
+    int32_t rc = check_lookup_state(ctx, exit, "smtm_lookup");
+    if (rc) return rc;
+    enqueue_lookup(ctx, exit, top_val, top_id, sims_out, static_cast<hipStream_t>(stream));
     rc = check_launch(ctx, "smtm_lookup");
     if (rc) return rc;
-    ctx->stage_done[l] = 2;
+    ctx->stage_done[exit - 1] = 2;
     return SMTM_OK;
 }
 
@@ -394,21 +441,10 @@ int32_t smtm_exit_compact(smtm_ctx* ctx, int32_t exit, int32_t* exit_ids, int32_
     const int l = exit - 1;
     if (ctx->batch == 0 || ctx->stage_done[l] != 2)
         return fail(ctx, SMTM_ERR_STATE, "smtm_exit_compact(%d) needs smtm_lookup(%d) first, once per batch", exit, exit);
-    if ((fmap_in != nullptr) != (fmap_out != nullptr))
-        return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_in and fmap_out must be given together");
-    if (fmap_out) {
-        if (row_bytes < 2 || (row_bytes & 1)) return fail(ctx, SMTM_ERR_SHAPE, "row_bytes %lld must be even and >= 2", (long long)row_bytes);
-        if (((reinterpret_cast<uintptr_t>(fmap_in) | reinterpret_cast<uintptr_t>(fmap_out)) & 15u) != 0)
-            return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_in and fmap_out must be 16-byte aligned");
-        if (fmap_in == fmap_out) return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_out must not overlap fmap_in");
-    }
-    const int32_t* cur = ctx->live[ctx->cur];
-    int32_t* nxt = ctx->live[ctx->cur ^ 1];
-    if (live_ids == cur || live_ids == nxt || row_ids == nxt)
-        return fail(ctx, SMTM_ERR_INVALID_ARG, "live_ids / row_ids alias the context's next live list");
+    rc = check_compact_args(ctx, live_ids, fmap_in, row_ids, fmap_out, row_bytes);
+    if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    launch_compact(ctx->decision, ctx->dlabel, cur, nxt, ctx->next_slots, ctx->counts, exit, exit_ids, exit_labels,
-                   exit_tier, n_exit_dev, live_ids, n_live_dev, ctx->res_layer, ctx->res_label, ctx->res_tier, st);
+    launch_compact(compact_args(ctx, exit, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids, n_live_dev), st);
     if (fmap_out)
         launch_gather_rows(fmap_in, row_ids, ctx->next_slots, ctx->counts, ctx->batch, fmap_out, row_bytes, st);
     rc = check_launch(ctx, "smtm_exit_compact");
@@ -418,26 +454,39 @@ int32_t smtm_exit_compact(smtm_ctx* ctx, int32_t exit, int32_t* exit_ids, int32_
     return SMTM_OK;
 }
 
+int32_t smtm_lookup_exit(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id,
+                         int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier, int32_t* n_exit_dev,
+                         int32_t* live_ids, int32_t* n_live_dev, const void* fmap_in, const int32_t* row_ids,
+                         void* fmap_out, int64_t row_bytes, void* stream) {
+    int32_t rc = check_lookup_state(ctx, exit, "smtm_lookup_exit");
+    if (rc) return rc;
+    rc = check_compact_args(ctx, live_ids, fmap_in, row_ids, fmap_out, row_bytes);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    enqueue_lookup(ctx, exit, top_val, top_id, nullptr, st);
+    launch_compact(compact_args(ctx, exit, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids, n_live_dev), st);
+    if (fmap_out)
+        launch_gather_rows(fmap_in, row_ids, ctx->next_slots, ctx->counts, ctx->batch, fmap_out, row_bytes, st);
+    rc = check_launch(ctx, "smtm_lookup_exit");
+    if (rc) return rc;
+    ctx->cur ^= 1;
+    ctx->stage_done[exit - 1] = 3;
+    return SMTM_OK;
+}
+
 int32_t smtm_stage(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
                    const int32_t* row_ids, int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
                    int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev, void* fmap_out, void* stream) {
     int32_t rc = check_encode_args(ctx, exit, fmap, dtype, H, W);
     if (rc) return rc;
     const int l = exit - 1;
-    if (fmap_out) {
-        if ((reinterpret_cast<uintptr_t>(fmap_out) & 15u) != 0) return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_out must be 16-byte aligned");
-        if (fmap_out == fmap) return fail(ctx, SMTM_ERR_INVALID_ARG, "fmap_out must not overlap fmap");
-    }
-    const int32_t* nxt = ctx->live[ctx->cur ^ 1];
-    if (live_ids == ctx->live[ctx->cur] || live_ids == nxt || row_ids == nxt)
-        return fail(ctx, SMTM_ERR_INVALID_ARG, "live_ids / row_ids alias the context's next live list");
+    const int64_t row_bytes = (int64_t)ctx->cfg.dims[l] * H * W * (dtype == SMTM_F16 ? 2 : 4);
+    rc = check_compact_args(ctx, live_ids, fmap_out ? fmap : nullptr, row_ids, fmap_out, row_bytes);
+    if (rc) return rc;
     rc = smtm_encode(ctx, exit, fmap, dtype, H, W, row_ids, nullptr, stream);
     if (rc) return rc;
-    rc = smtm_lookup(ctx, exit, nullptr, nullptr, nullptr, stream);
-    if (rc) return rc;
-    const int64_t row_bytes = (int64_t)ctx->cfg.dims[l] * H * W * (dtype == SMTM_F16 ? 2 : 4);
-    return smtm_exit_compact(ctx, exit, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids, n_live_dev,
-                             fmap_out ? fmap : nullptr, row_ids, fmap_out, row_bytes, stream);
+    return smtm_lookup_exit(ctx, exit, nullptr, nullptr, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids,
+                            n_live_dev, fmap_out ? fmap : nullptr, row_ids, fmap_out, row_bytes, stream);
 }
 
 const int32_t* smtm_live_ids(const smtm_ctx* ctx) { return ctx ? ctx->live[ctx->cur] : nullptr; }

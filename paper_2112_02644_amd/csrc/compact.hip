@@ -37,25 +37,20 @@ void launch_begin_batch(float* SA, int n, int batch, int32_t* live, int32_t* res
                        res_label, res_tier, counts);
 }
 
-// One block of 1024 threads (16 wavefronts) walks the live list in chunks of 1024 slots.
-__global__ __launch_bounds__(1024) void k_compact(
-    const int32_t* __restrict__ decision, const int32_t* __restrict__ label,
-    const int32_t* __restrict__ frame_ids, int32_t* __restrict__ next_ids,
-    int32_t* __restrict__ next_slots, Counts* __restrict__ counts, int exit_index,
-    int32_t* __restrict__ exit_ids, int32_t* __restrict__ exit_labels,
-    int32_t* __restrict__ exit_tier, int32_t* __restrict__ n_exit_dev,
-    int32_t* __restrict__ live_ids_user, int32_t* __restrict__ n_live_dev,
-    int32_t* __restrict__ res_layer, int32_t* __restrict__ res_label, int32_t* __restrict__ res_tier) {
-    __shared__ int w_exit[16], w_t1[16];
+// Stable partition of the live list by one block: wavefront ballot + popcount prefix, an LDS scan
+// over the block's wavefronts, running bases across chunks of the list.
+template <int NW>                                        // wavefronts in the block
+__device__ __forceinline__ void compact_block(const CompactArgs& a, int n_live) {
+    __shared__ int w_exit[NW], w_t1[NW];
     __shared__ int base_exit, base_t1;
+    constexpr int BS = NW * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n_live = counts->n_live;
     if (tid == 0) { base_exit = 0; base_t1 = 0; }
     __syncthreads();
-    for (int c0 = 0; c0 < n_live; c0 += 1024) {          // uniform over the block
+    for (int c0 = 0; c0 < n_live; c0 += BS) {            // uniform over the block
         const int slot = c0 + tid;
         const bool valid = slot < n_live;
-        const int d = valid ? decision[slot] : 0;
+        const int d = valid ? a.decision[slot] : 0;
         const bool ex = valid && d != 0;
         const unsigned long long m_ex = __ballot(ex);
         const unsigned long long m_t1 = __ballot(valid && d == 1);
@@ -64,26 +59,27 @@ __global__ __launch_bounds__(1024) void k_compact(
         if (lane == 0) { w_exit[wave] = __popcll(m_ex); w_t1[wave] = __popcll(m_t1); }
         __syncthreads();
         int off_ex = 0, tot_ex = 0, tot_t1 = 0;
-        for (int w = 0; w < 16; ++w) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
             if (w < wave) off_ex += w_exit[w];
             tot_ex += w_exit[w]; tot_t1 += w_t1[w];
         }
         const int be = base_exit;
         if (valid) {
-            const int frame = frame_ids[slot];
+            const int frame = a.frame_ids[slot];
             if (ex) {
                 const int pos = be + off_ex + pre_ex;
-                const int lab = label[slot];
-                if (exit_ids) exit_ids[pos] = frame;
-                if (exit_labels) exit_labels[pos] = lab;
-                if (exit_tier) exit_tier[pos] = d;
-                res_layer[frame] = exit_index; res_label[frame] = lab; res_tier[frame] = d;
+                const int lab = a.label[slot];
+                if (a.exit_ids) a.exit_ids[pos] = frame;
+                if (a.exit_labels) a.exit_labels[pos] = lab;
+                if (a.exit_tier) a.exit_tier[pos] = d;
+                a.res_layer[frame] = a.exit_index; a.res_label[frame] = lab; a.res_tier[frame] = d;
             } else {
                 // survivors before this slot = slots before it minus exits before it
                 const int pos = slot - (be + off_ex + pre_ex);
-                next_ids[pos] = frame;
-                next_slots[pos] = slot;
-                if (live_ids_user) live_ids_user[pos] = frame;
+                a.next_ids[pos] = frame;
+                a.next_slots[pos] = slot;
+                if (a.live_ids_user) a.live_ids_user[pos] = frame;
             }
         }
         __syncthreads();
@@ -92,24 +88,23 @@ __global__ __launch_bounds__(1024) void k_compact(
     }
     if (tid == 0) {
         const int ne = base_exit, nl = n_live - base_exit;
-        counts->stats[exit_index - 1][0] = n_live;
-        counts->stats[exit_index - 1][1] = base_t1;
-        counts->stats[exit_index - 1][2] = ne - base_t1;
-        counts->n_exit = ne;
-        counts->n_live = nl;
-        if (n_exit_dev) *n_exit_dev = ne;
-        if (n_live_dev) *n_live_dev = nl;
+        a.counts->stats[a.exit_index - 1][0] = n_live;
+        a.counts->stats[a.exit_index - 1][1] = base_t1;
+        a.counts->stats[a.exit_index - 1][2] = ne - base_t1;
+        a.counts->n_exit = ne;
+        a.counts->n_live = nl;
+        if (a.n_exit_dev) *a.n_exit_dev = ne;
+        if (a.n_live_dev) *a.n_live_dev = nl;
     }
 }
 
-void launch_compact(const int32_t* decision, const int32_t* label, const int32_t* frame_ids,
-                    int32_t* next_ids, int32_t* next_slots, Counts* counts, int exit_index,
-                    int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier, int32_t* n_exit_dev,
-                    int32_t* live_ids_user, int32_t* n_live_dev, int32_t* res_layer,
-                    int32_t* res_label, int32_t* res_tier, hipStream_t st) {
-    hipLaunchKernelGGL(k_compact, dim3(1), dim3(1024), 0, st, decision, label, frame_ids, next_ids,
-                       next_slots, counts, exit_index, exit_ids, exit_labels, exit_tier, n_exit_dev,
-                       live_ids_user, n_live_dev, res_layer, res_label, res_tier);
+// One block of 1024 threads (16 wavefronts) walks the live list in chunks of 1024 slots.
+__global__ __launch_bounds__(1024) void k_compact(CompactArgs a) {
+    compact_block<16>(a, a.counts->n_live);
+}
+
+void launch_compact(const CompactArgs& args, hipStream_t st) {
+    hipLaunchKernelGGL(k_compact, dim3(1), dim3(1024), 0, st, args);
 }
 
 // Gather of the survivors' feature-map rows: new slot s copies the row that old slot

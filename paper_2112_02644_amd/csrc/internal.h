@@ -19,6 +19,18 @@ struct Counts {
     int32_t stats[SMTM_MAX_EXITS][4];     // per exit point: live in, released tier 1, released tier 2, spare
 };
 
+struct CompactArgs {                      // everything the stable partition reads and writes
+    const int32_t* decision;              // [slots] 0 continue, 1 / 2 released by tier 1 / 2
+    const int32_t* label;                 // [slots]
+    const int32_t* frame_ids;             // [slots] current live list
+    int32_t* next_ids;                    // survivors' frame ids (the next live list)
+    int32_t* next_slots;                  // survivors' old slots (for the row gather)
+    Counts* counts;
+    int exit_index;                       // 1-based
+    int32_t *exit_ids, *exit_labels, *exit_tier, *n_exit_dev, *live_ids_user, *n_live_dev;   // caller's, may be NULL
+    int32_t *res_layer, *res_label, *res_tier;                                               // per-frame results
+};
+
 constexpr int kWave = 64;
 constexpr int kKPad = 64;                 // fp16 operand rows are zero-padded to a multiple of this many columns
 constexpr int kRowPad = 128;              // fp16 operand matrices are padded to a multiple of this many rows
@@ -50,11 +62,7 @@ void launch_top2_decide(const float* SA, const int32_t* frame_ids, const Counts*
 // ---- compact.hip ------------------------------------------------------------------------
 void launch_begin_batch(float* SA, int n, int batch, int32_t* live, int32_t* res_layer,
                         int32_t* res_label, int32_t* res_tier, Counts* counts, hipStream_t st);
-void launch_compact(const int32_t* decision, const int32_t* label, const int32_t* frame_ids,
-                    int32_t* next_ids, int32_t* next_slots, Counts* counts, int exit_index,
-                    int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier, int32_t* n_exit_dev,
-                    int32_t* live_ids_user, int32_t* n_live_dev, int32_t* res_layer,
-                    int32_t* res_label, int32_t* res_tier, hipStream_t st);
+void launch_compact(const CompactArgs& args, hipStream_t st);
 void launch_gather_rows(const void* src, const int32_t* row_ids, const int32_t* next_slots,
                         const Counts* counts, int max_rows, void* dst, int64_t row_bytes,
                         hipStream_t st);

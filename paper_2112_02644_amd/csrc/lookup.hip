@@ -211,12 +211,10 @@ __global__ __launch_bounds__(256) void k_score_mfma(
     const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows, int n,
     float weight, float* __restrict__ SA, float* __restrict__ sims_out) {
     constexpr int BM = 64 * WM, BN = 64 * WN;
-    __shared__ _Float16 As[BM * MF_LD];
-    __shared__ _Float16 Bs[BN * MF_LD];
-    int n_live = counts->n_live;
-    if (n_live > max_rows) n_live = max_rows;
+    constexpr int RA = BM / 32, RB = BN / 32;            // 16-byte chunks each thread moves per stage
+    __shared__ _Float16 As[2][BM * MF_LD];               // double buffered: the next K stage is fetched
+    __shared__ _Float16 Bs[2][BN * MF_LD];               // from L2 while the current one is multiplied
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    if (m0 >= n_live) return;                            // uniform over the block
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lk = (lane >> 5) * 8;
@@ -231,33 +229,79 @@ __global__ __launch_bounds__(256) void k_score_mfma(
 
     // loader: each 64-half row of a stage is 8 chunks of 16 B; thread -> (row, chunk)
     const int ld_row = tid >> 3, ld_chunk = tid & 7;
-    for (int k0 = 0; k0 < Cp; k0 += MF_K) {
+    const _Float16* a_src = A + (int64_t)(m0 + ld_row) * Cp + ld_chunk * 8;
+    const _Float16* b_src = B + (int64_t)(n0 + ld_row) * Cp + ld_chunk * 8;
+    const int lds_off = ld_row * MF_LD + ld_chunk * 8;
+    // Two register sets: while stage st is multiplied out of LDS, the loads of stage st+2 are in
+    // flight and stage st+1 (loaded one iteration earlier) is written to the other LDS buffer.
+    u32x4 ra0[RA], rb0[RB], ra1[RA], rb1[RB];
+    const int n_stage = Cp / MF_K;
+    auto fetch = [&](u32x4* ra, u32x4* rb, int stage) {
+        const int k1 = stage * MF_K;
 #pragma unroll
-        for (int r = 0; r < BM; r += 32) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(A + (int64_t)(m0 + r + ld_row) * Cp + k0 + ld_chunk * 8);
-            *reinterpret_cast<u32x4*>(&As[(r + ld_row) * MF_LD + ld_chunk * 8]) = v;
-        }
+        for (int r = 0; r < RA; ++r) ra[r] = *reinterpret_cast<const u32x4*>(a_src + (int64_t)r * 32 * Cp + k1);
 #pragma unroll
-        for (int r = 0; r < BN; r += 32) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(B + (int64_t)(n0 + r + ld_row) * Cp + k0 + ld_chunk * 8);
-            *reinterpret_cast<u32x4*>(&Bs[(r + ld_row) * MF_LD + ld_chunk * 8]) = v;
-        }
-        __syncthreads();
+        for (int r = 0; r < RB; ++r) rb[r] = *reinterpret_cast<const u32x4*>(b_src + (int64_t)r * 32 * Cp + k1);
+    };
+    auto stash = [&](const u32x4* ra, const u32x4* rb, int buf) {
+#pragma unroll
+        for (int r = 0; r < RA; ++r) *reinterpret_cast<u32x4*>(&As[buf][lds_off + r * 32 * MF_LD]) = ra[r];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) *reinterpret_cast<u32x4*>(&Bs[buf][lds_off + r * 32 * MF_LD]) = rb[r];
+    };
+    auto multiply = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < MF_K; ks += 16) {
             half8_t a[WM], b[WN];
 #pragma unroll
             for (int i = 0; i < WM; ++i)
-                a[i] = *reinterpret_cast<const half8_t*>(&As[((wm * WM + i) * 32 + lrow) * MF_LD + ks + lk]);
+                a[i] = *reinterpret_cast<const half8_t*>(&As[buf][((wm * WM + i) * 32 + lrow) * MF_LD + ks + lk]);
 #pragma unroll
             for (int j = 0; j < WN; ++j)
-                b[j] = *reinterpret_cast<const half8_t*>(&Bs[((wn * WN + j) * 32 + lrow) * MF_LD + ks + lk]);
+                b[j] = *reinterpret_cast<const half8_t*>(&Bs[buf][((wn * WN + j) * 32 + lrow) * MF_LD + ks + lk]);
 #pragma unroll
             for (int i = 0; i < WM; ++i)
 #pragma unroll
                 for (int j = 0; j < WN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
+    };
+    // the operand loads are in bounds whatever the live count is (padded matrices), so they are
+    // issued before the live count is waited for
+    fetch(ra0, rb0, 0);
+    if (n_stage > 1) fetch(ra1, rb1, 1);
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    if (m0 >= n_live) return;                            // uniform over the block
+    stash(ra0, rb0, 0);
+    __syncthreads();
+
+    // old SA values of this thread's outputs, fetched while the K loop runs
+    float sa_old[WM][WN][16];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            const int cls = n0 + (wn * WN + j) * 32 + (lane & 31);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int slot = m0 + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                sa_old[i][j][e] = 0.f;
+                if (slot < n_live && cls < n) sa_old[i][j][e] = SA[(int64_t)frame_ids[slot] * n + cls];
+            }
+        }
+
+    for (int st = 0; st < n_stage; st += 2) {            // two stages per trip so the register sets are static
+        // even stage: LDS buffer 0 holds it, set 1 holds stage st+1
+        if (st + 2 < n_stage) fetch(ra0, rb0, st + 2);
+        multiply(0);
+        if (st + 1 < n_stage) stash(ra1, rb1, 1);        // buffer 1 was last read before the previous barrier
+        __syncthreads();
+        if (st + 1 >= n_stage) break;                    // uniform
+        // odd stage: LDS buffer 1 holds it, set 0 holds stage st+2
+        if (st + 3 < n_stage) fetch(ra1, rb1, st + 3);
+        multiply(1);
+        if (st + 2 < n_stage) stash(ra0, rb0, 0);
         __syncthreads();
     }
 
@@ -272,7 +316,7 @@ __global__ __launch_bounds__(256) void k_score_mfma(
                 if (slot < n_live && cls < n) {
                     const float s = acc[i][j][e];
                     const int64_t frame = frame_ids[slot];
-                    SA[frame * n + cls] += weight * s;
+                    SA[frame * n + cls] = sa_old[i][j][e] + weight * s;
                     if (sims_out) sims_out[(int64_t)slot * n + cls] = s;
                 }
             }

@@ -32,6 +32,8 @@ __device__ __forceinline__ u128 shfl_xor_u128(u128 x, int off) {
 // else TS_j + batch.  Both saturate at 2^32 - 1.  Also leaves every class's score and the
 // 128-bit total of the scores (total[0] low, total[1] high) and clears the policy counter.
 // Single block of 1024 threads.
+constexpr int kLdsClasses = 4096;
+
 __global__ __launch_bounds__(1024) void k_tables_update(const int32_t* __restrict__ label, int batch,
                                                         int n, uint32_t W, uint32_t* __restrict__ FT,
                                                         uint32_t* __restrict__ TS,
@@ -41,23 +43,31 @@ __global__ __launch_bounds__(1024) void k_tables_update(const int32_t* __restric
                                                         uint64_t* __restrict__ total,
                                                         int32_t* __restrict__ below) {
     __shared__ uint64_t red_lo[16], red_hi[16];
+    __shared__ uint32_t l_cnt[kLdsClasses];
+    __shared__ int32_t l_last[kLdsClasses];
     const int tid = threadIdx.x;
-    for (int i = tid; i < n; i += 1024) { cls_cnt[i] = 0; cls_last[i] = -1; }
+    const bool in_lds = n <= kLdsClasses;                // histogram in LDS when the classes fit, else in global memory
+    for (int i = tid; i < n; i += 1024) {
+        if (in_lds) { l_cnt[i] = 0; l_last[i] = -1; } else { cls_cnt[i] = 0; cls_last[i] = -1; }
+    }
     __syncthreads();
     for (int b = tid; b < batch; b += 1024) {
         const int j = label[b];
         if (j >= 0 && j < n) {
-            atomicAdd(&cls_cnt[j], 1u);
-            atomicMax(&cls_last[j], b);
+            if (in_lds) { atomicAdd(&l_cnt[j], 1u); atomicMax(&l_last[j], b); }
+            else { atomicAdd(&cls_cnt[j], 1u); atomicMax(&cls_last[j], b); }
         }
     }
     __syncthreads();
     u128 part = 0;
     for (int i = tid; i < n; i += 1024) {
-        uint64_t ft = (uint64_t)FT[i] + cls_cnt[i];
+        const uint32_t cnt_i = in_lds ? l_cnt[i] : cls_cnt[i];
+        const int32_t last_i = in_lds ? l_last[i] : cls_last[i];
+        if (in_lds) cls_cnt[i] = cnt_i;                  // the centre update reads the counts
+        uint64_t ft = (uint64_t)FT[i] + cnt_i;
         if (ft > 0xffffffffull) ft = 0xffffffffull;
         uint64_t ts;
-        if (cls_last[i] >= 0) ts = (uint64_t)(batch - 1 - cls_last[i]);
+        if (last_i >= 0) ts = (uint64_t)(batch - 1 - last_i);
         else ts = (uint64_t)TS[i] + (uint64_t)batch;
         if (ts > 0xffffffffull) ts = 0xffffffffull;
         FT[i] = (uint32_t)ft;
@@ -128,14 +138,18 @@ __global__ __launch_bounds__(256) void k_centres_update(CentreTables tabs, int n
     overflow = cnt > kListCap;
     const float m_old = (float)tabs.mcount[l0][j];
     float ss = 0.f;
+    // thread = channel (256 at a time, coalesced rows), frames of the list in ascending order,
+    // eight rows in flight
     for (int c = tid; c < C; c += 256) {
         float sum = 0.f;
         if (!overflow) {
             int i = 0;
-            for (; i + 4 <= cnt; i += 4) {               // four independent loads in flight
-                const float a0 = sv[(int64_t)list[i] * C + c], a1 = sv[(int64_t)list[i + 1] * C + c];
-                const float a2 = sv[(int64_t)list[i + 2] * C + c], a3 = sv[(int64_t)list[i + 3] * C + c];
-                sum += a0; sum += a1; sum += a2; sum += a3;
+            for (; i + 8 <= cnt; i += 8) {
+                float a[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) a[u] = sv[(int64_t)list[i + u] * C + c];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sum += a[u];
             }
             for (; i < cnt; ++i) sum += sv[(int64_t)list[i] * C + c];
         } else {                                         // more frames of one class than the list holds
@@ -177,24 +191,35 @@ void launch_centres_update(const CentreTables& tabs, int n_exits, int n, const i
 //   k       = 1 + number of classes whose prefix is still below CL * total
 //             (the prefix share is non-decreasing along the order), clamped to [hot_min, hot_max]
 // k_policy_rank: 16 lanes per class split the scan over all classes and combine with shuffles.
+constexpr int kRankTile = 2048;            // scores staged per pass (16 KB of LDS)
+
 __global__ __launch_bounds__(256) void k_policy_rank(const uint64_t* __restrict__ score,
                                                      const uint64_t* __restrict__ total, int n,
                                                      uint32_t cl_num, uint32_t cl_den,
                                                      int32_t* __restrict__ order,
                                                      int32_t* __restrict__ below) {
+    __shared__ uint64_t tile[kRankTile];
     const int tid = threadIdx.x, sub = tid & 15;
     const int i = blockIdx.x * 16 + (tid >> 4);
+    const bool valid = i < n;
+    const uint64_t si = valid ? score[i] : 0;            // issued before the total is needed
     const u128 tot = ((u128)total[1] << 64) | total[0];
     if (tot == 0) return;                                // no history: nothing changes (uniform)
-    const bool valid = i < n;
-    const uint64_t si = valid ? score[i] : 0;
     int rank = 0;
     u128 prefix = 0;
-    if (valid) {
-        for (int j = sub; j < n; j += 16) {
-            const uint64_t sj = score[j];
-            if (sj > si || (sj == si && j < i)) { ++rank; prefix += sj; }
+    for (int j0 = 0; j0 < n; j0 += kRankTile) {          // uniform trip count
+        const int len = n - j0 < kRankTile ? n - j0 : kRankTile;
+        for (int j = tid; j < len; j += 256) tile[j] = score[j0 + j];
+        __syncthreads();
+        if (valid) {
+#pragma unroll 4
+            for (int j = sub; j < len; j += 16) {
+                const uint64_t sj = tile[j];
+                const int jj = j0 + j;
+                if (sj > si || (sj == si && jj < i)) { ++rank; prefix += sj; }
+            }
         }
+        __syncthreads();
     }
     for (int off = 8; off > 0; off >>= 1) {
         rank += __shfl_xor(rank, off, 64);

@@ -94,6 +94,7 @@ def load_library():
         "smtm_encode": [vp, i32, vp, i32, i32, i32, vp, vp, vp],
         "smtm_lookup": [vp, i32, vp, vp, vp, vp],
         "smtm_exit_compact": [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp],
+        "smtm_lookup_exit": [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp],
         "smtm_stage": [vp, i32, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp],
         "smtm_batch_results": [vp, vp, vp, vp, vp],
         "smtm_read_counts": [vp, vp, vp, vp],
@@ -224,6 +225,14 @@ class Smtm:
         self._ck(self.lib.smtm_exit_compact(self._h, exit, _ptr(exit_ids), _ptr(exit_labels), _ptr(exit_tier),
                                             _ptr(n_exit_dev), _ptr(live_ids), _ptr(n_live_dev), _ptr(fmap_in),
                                             _ptr(row_ids), _ptr(fmap_out), int(row_bytes), self._st(stream)))
+
+    def lookup_exit(self, exit: int, top_val=None, top_id=None, exit_ids=None, exit_labels=None,
+                    exit_tier=None, n_exit_dev=None, live_ids=None, n_live_dev=None, fmap_in=None,
+                    row_ids=None, fmap_out=None, row_bytes: int = 0, stream=None):
+        self._ck(self.lib.smtm_lookup_exit(self._h, exit, _ptr(top_val), _ptr(top_id), _ptr(exit_ids),
+                                           _ptr(exit_labels), _ptr(exit_tier), _ptr(n_exit_dev), _ptr(live_ids),
+                                           _ptr(n_live_dev), _ptr(fmap_in), _ptr(row_ids), _ptr(fmap_out),
+                                           int(row_bytes), self._st(stream)))
 
     def stage(self, exit: int, fmap, row_ids=None, exit_ids=None, exit_labels=None, exit_tier=None,
               n_exit_dev=None, live_ids=None, n_live_dev=None, fmap_out=None, stream=None,

@@ -106,7 +106,8 @@ def check_batch(ctx: Smtm, mem: O.Memory, w: Workload, fmaps: List[torch.Tensor]
                 report: Optional[ParityReport] = None) -> ParityReport:
     """One batch through both sides.  mode: "row_ids" (full-batch tensors addressed through the
     context's live list) or "dense" (each exit point gets a tensor holding only the live frames,
-    and the survivors' maps are gathered for the next block).  fused: use smtm_stage."""
+    and the survivors' maps are gathered for the next block).  fused: False = the three calls,
+    "lookup_exit" = smtm_encode + smtm_lookup_exit, True = smtm_stage."""
     rep = report or ParityReport()
     dev = fmaps[0].device
     B = fmaps[0].shape[0]
@@ -141,10 +142,17 @@ def check_batch(ctx: Smtm, mem: O.Memory, w: Workload, fmaps: List[torch.Tensor]
         top_val = torch.full((B, 2, 2), float("nan"), dtype=torch.float32, device=dev)
         top_id = torch.full((B, 2), -7, **i32)
         sims = torch.full((B, n), float("nan"), dtype=torch.float32, device=dev) if check_sims else None
-        gather = torch.full((max(n_live, 1),) + tuple(F_full.shape[1:]), 0, dtype=F_full.dtype, device=dev) \
-            if mode == "dense" else None
+        # survivors' feature maps are gathered in both modes (through the row list in "row_ids" mode)
+        gather = torch.full((max(n_live, 1),) + tuple(F_full.shape[1:]), 0, dtype=F_full.dtype, device=dev)
         row_bytes = C * H * W * F_full.element_size()
-        if fused:
+        if fused == "lookup_exit":
+            # encode, then lookup + exit/compact in one call (no similarities out)
+            ctx.encode(l, F_in, row_ids=row_ids, sv_out=sv_out)
+            ctx.lookup_exit(l, top_val=top_val, top_id=top_id, exit_ids=exit_ids, exit_labels=exit_labels,
+                            exit_tier=exit_tier, n_exit_dev=n_exit_dev, live_ids=live_out,
+                            n_live_dev=n_live_dev, fmap_in=F_in if gather is not None else None,
+                            row_ids=row_ids, fmap_out=gather, row_bytes=row_bytes)
+        elif fused:
             ctx.stage(l, F_in, row_ids=row_ids, exit_ids=exit_ids, exit_labels=exit_labels,
                       exit_tier=exit_tier, n_exit_dev=n_exit_dev, live_ids=live_out,
                       n_live_dev=n_live_dev, fmap_out=gather)
@@ -162,8 +170,10 @@ def check_batch(ctx: Smtm, mem: O.Memory, w: Workload, fmaps: List[torch.Tensor]
 
         # ---- oracle on the same bits, from the library's live set (teacher forcing)
         F_host = F_in.cpu().numpy()
+        full = fused in (False, "lookup_exit")           # semantic vectors and top-2 values were captured
+        with_sims = check_sims and fused is False
         ref = mem.stage(l, F_host, row_ids=rows_host.astype(np.int32) if mode != "dense" else None,
-                        live=live, want_sims=check_sims and not fused)
+                        live=live, want_sims=with_sims)
 
         g_exit = exit_ids[:n_exit].cpu().numpy(); g_lab = exit_labels[:n_exit].cpu().numpy()
         g_tier = exit_tier[:n_exit].cpu().numpy(); g_live = live_out[:n_live_next].cpu().numpy()
@@ -179,7 +189,7 @@ def check_batch(ctx: Smtm, mem: O.Memory, w: Workload, fmaps: List[torch.Tensor]
         assert np.all((g_tier == 1) | (g_tier == 2))
         assert int(exit_ids[n_exit:].eq(-7).all()) or True
 
-        if not fused:
+        if full:
             # ---- semantic vectors
             sv_g = sv_out[:n_live].cpu().numpy().astype(np.float64)
             assert np.isnan(sv_out[n_live:].cpu().numpy()).all(), "rows past the live count were written"
@@ -191,7 +201,7 @@ def check_batch(ctx: Smtm, mem: O.Memory, w: Workload, fmaps: List[torch.Tensor]
             rep.max_sv_err = max(rep.max_sv_err, float(err.max(initial=0.0)))
             assert err.max(initial=0.0) <= SV_RTOL, f"exit {l}: semantic vector error {err.max():.3e}"
             # ---- similarities
-            if check_sims:
+            if with_sims:
                 s_g = sims[:n_live].cpu().numpy().astype(np.float64)
                 tol = rtol * np.maximum(np.abs(ref["sims"]), ref["sims_scale"])
                 e = np.abs(s_g - ref["sims"]) / np.maximum(tol, 1e-300)
@@ -242,7 +252,7 @@ def check_batch(ctx: Smtm, mem: O.Memory, w: Workload, fmaps: List[torch.Tensor]
         # ---- gathered survivors: byte-identical rows
         if gather is not None and n_live_next:
             keep = np.flatnonzero(dec_gpu == 0)
-            want_rows = F_in[torch.from_numpy(keep.astype(np.int64)).to(dev)]
+            want_rows = F_in[torch.from_numpy(np.asarray(rows_host)[keep].astype(np.int64)).to(dev)]
             assert torch.equal(gather[:n_live_next].view(torch.int16 if F_full.element_size() == 2 else torch.int32),
                                want_rows.view(torch.int16 if F_full.element_size() == 2 else torch.int32))
 

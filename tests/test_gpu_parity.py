@@ -120,7 +120,8 @@ def test_tiny_tau_sweep(tau, tiers):
         assert rep.tier_hist[2] == 0
 
 
-@pytest.mark.parametrize("mode,fused", [("dense", False), ("row_ids", True), ("dense", True)])
+@pytest.mark.parametrize("mode,fused", [("dense", False), ("row_ids", True), ("dense", True),
+                                        ("row_ids", "lookup_exit"), ("dense", "lookup_exit")])
 def test_tiny_modes(mode, fused):
     _say("tiny", mode, fused)
     rep, _ = _one_batch(configs.TINY, mode=mode, fused=fused)
@@ -135,7 +136,9 @@ def test_tiny_mfma_path_on_fp32_maps_within_fp16_tolerance():
 # ------------------------------------------------------------------ workload 2: ResNet-18-shaped
 
 @pytest.mark.parametrize("mode,fused,path", [("row_ids", False, SCORE_AUTO), ("dense", False, SCORE_AUTO),
-                                             ("row_ids", True, SCORE_AUTO), ("row_ids", False, SCORE_FP32)])
+                                             ("row_ids", True, SCORE_AUTO), ("row_ids", False, SCORE_FP32),
+                                             ("row_ids", "lookup_exit", SCORE_AUTO),
+                                             ("dense", "lookup_exit", SCORE_FP32)])
 def test_resnet18(mode, fused, path):
     _say("resnet18", mode, fused, path)
     w = configs.RESNET18
@@ -180,6 +183,14 @@ def test_resnet50_fused_dense_full_size():
     assert sum(rep.exit_hist) == w.batch
 
 
+def test_resnet50_lookup_exit_full_size():
+    # the launch configuration bench.py times: encode + lookup_exit on full-batch tensors with the gather
+    w = configs.RESNET50
+    _say("resnet50 encode + lookup_exit")
+    rep, _ = _one_batch(w, mode="row_ids", fused="lookup_exit", check_sims=False)
+    assert sum(rep.exit_hist) == w.batch and rep.in_band_flips <= w.batch // 50
+
+
 def test_mobilenetv2_full_size():
     w = configs.MOBILENETV2
     _say("mobilenetv2 full size")
@@ -201,7 +212,8 @@ def _run_stream(w, n_batches, check_every=1):
     worst_centre = 0.0
     for b in range(n_batches):
         fm = streams.batch_feature_maps(w, cents, ls, b, DEV)
-        P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), check_sims=(b == 0), report=rep)
+        P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), check_sims=(b == 0), report=rep,
+                      fused=("lookup_exit" if b % 2 else False), mode=("dense" if b % 3 == 2 else "row_ids"))
         # frames that ran to the end get the stream's own label (stand-in for the classifier),
         # but do not move centres: only exited classes are updated
         truth = ls.label[b * w.batch:(b + 1) * w.batch]
