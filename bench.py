@@ -24,6 +24,25 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
+# HBM bytes per launch of the dominant kernel from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
+# profiles/encode_direct_f16_hbm_traffic.txt (same command, same workload).  Reported only while the kernel's
+# source is the one the counters were taken on; otherwise the field is null.
+TRAFFIC = {"workload": "resnet50", "bytes_per_launch": 972828895.0,
+           "encode_sha256": "789fdebb3af62aca5853e9faf68d60074928e439c798f13e9fd36d53def7d8ce"}
+
+
+def measured_traffic(workload: str):
+    import hashlib
+    from pathlib import Path
+    src = Path(__file__).resolve().parent / "paper_2112_02644_amd" / "csrc" / "encode.hip"
+    try:
+        sha = hashlib.sha256(src.read_bytes()).hexdigest()
+    except OSError:
+        return None
+    if workload != TRAFFIC["workload"] or sha != TRAFFIC["encode_sha256"]:
+        return None
+    return TRAFFIC["bytes_per_launch"]
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -139,8 +158,8 @@ def main() -> int:
                                  "memory update every batch",
                    "exits_per_exit_point": exits.mean(axis=0).round(1).tolist(),
                    "ran_to_end": float(live[:, -1].mean())},
-        "roofline": {"bound": "hbm", "kernel": "k_encode_direct<f16,16B>", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+        "roofline": {"bound": "hbm", "kernel": f"k_encode_direct<{w.dtype},16B>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "cpu_baseline": {"value": ns / cpu_s, "unit": "frames/s", "cores": cores, "kind": "oracle",
                          "sample": f"first {ns} frames of the same batch, all {L} exit points and the memory "
