@@ -132,7 +132,22 @@ def main() -> int:
     path_bytes = (enc_bytes.sum(axis=1) + gat_bytes.sum(axis=1)).mean()   # algorithmic bytes per step: encode stream + gather (read + write)
     stage_gbs = path_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # ---- CPU oracle on a bounded sample of the same batch (all host threads it gets)
+    # ---- after the timed region: the exit-point-1 stage alone (encode + lookup + exit/compact on the full
+    # batch, no gather), bracketed by events, as a fraction of the HBM roofline
+    reps = 10
+    sev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for r in range(reps):
+        ctx.begin_batch(B)
+        sev[r][0].record()
+        ctx.encode(1, fmaps[0], row_ids=ctx.live_ids())
+        ctx.lookup_exit(1)
+        sev[r][1].record()
+        # keep the L2 / memory-side cache from holding the start of the tensor for the next repetition
+        ctx.encode(2, fmaps[1], row_ids=ctx.live_ids())
+    torch.cuda.synchronize()
+    stage1_ms = float(np.median([a.elapsed_time(b) for a, b in sev]))
+    stage1_bytes = B * per_exit_bytes[0]
+
     from oracle import smtm_oracle as O
     ns = min(args.cpu_sample, B)
     host = [f[:ns].cpu().numpy() for f in fmaps]
@@ -168,6 +183,9 @@ def main() -> int:
         "encode_gbs_per_exit_point": [None if np.isnan(t) else round(float(b / (t * 1e-3) / 1e9), 1)
                                       for b, t in zip(enc_bytes.mean(axis=0), enc_ms.mean(axis=0))],
         "path_hbm_frac": stage_gbs / HBM_PEAK_GBS,
+        "exit1_stage": {"what": "encode + lookup + exit/compact of exit point 1 on the full batch, no gather",
+                        "ms": stage1_ms, "GB/s": stage1_bytes / (stage1_ms * 1e-3) / 1e9,
+                        "hbm_frac": stage1_bytes / (stage1_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         # survivors after each exit point for every step run (warm-up included), so that per-dispatch
         # byte counts of a profile of this command can be reconstructed
         "survivors_log": live_log.cpu().numpy().tolist(),

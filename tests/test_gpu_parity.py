@@ -423,3 +423,63 @@ def test_call_order_and_argument_errors():
     assert e.value.code == 2
     torch.cuda.synchronize()
     ctx.close()
+
+
+# ------------------------------------------------------------------ the hot calls can be captured in a HIP graph
+
+def test_step_captured_in_a_graph_replays_like_eager():
+    # Small workloads are launch-bound; a caller can capture a whole step (the hot calls only enqueue
+    # kernels on the caller's stream).  Every replay must give what the eager calls give, bit for bit.
+    w = configs.RESNET18
+    cents = streams.centroids(w); ls = streams.labels(w)
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    B, L = w.batch, w.n_exits
+
+    def make():
+        ctx = P.make_ctx(dataclasses.replace(w, hot_min=4, hot_max=64), cents, ls.initial_hot)
+        bufs = dict(gather=[torch.zeros_like(f) for f in fm],
+                    res=[torch.zeros(B, dtype=torch.int32, device=DEV) for _ in range(3)],
+                    nlive=torch.zeros(L, dtype=torch.int32, device=DEV))
+        return ctx, bufs
+
+    def step(ctx, bufs):
+        ctx.begin_batch(B)
+        for l in range(1, L + 1):
+            F = fm[l - 1]
+            ids = ctx.live_ids()
+            ctx.encode(l, F, row_ids=ids)
+            ctx.lookup_exit(l, n_live_dev=bufs["nlive"].data_ptr() + 4 * (l - 1), fmap_in=F, row_ids=ids,
+                            fmap_out=bufs["gather"][l - 1], row_bytes=F[0].numel() * F.element_size())
+        ctx.batch_results(*bufs["res"])
+        ctx.cache_update(bufs["res"][1], bufs["res"][0], B)
+
+    def snapshot(ctx, bufs):
+        torch.cuda.synchronize()
+        cen = [ctx.memory_export(l) for l in range(1, L + 1)]
+        return ([r.cpu().clone() for r in bufs["res"]] + [bufs["nlive"].cpu().clone()] +
+                [g.cpu().clone() for g in bufs["gather"]], cen, ctx.tables_export())
+
+    eager_ctx, eager_bufs = make()
+    graph_ctx, graph_bufs = make()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                 # the live-list pointers alternate every exit point: with an
+        step(graph_ctx, graph_bufs)               # even number of exit points a step starts where it began
+    torch.cuda.current_stream().wait_stream(side)
+    step(eager_ctx, eager_bufs)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(graph_ctx, graph_bufs)
+    for rep in range(3):
+        g.replay()
+        step(eager_ctx, eager_bufs)
+        scratch = torch.randn(1 << 20, device=DEV).sum().item()      # unrelated eager work and a sync between replays
+        a, b = snapshot(graph_ctx, graph_bufs), snapshot(eager_ctx, eager_bufs)
+        for x, y in zip(a[0], b[0]):
+            assert torch.equal(x.view(torch.int16) if x.element_size() == 2 else x, y.view(torch.int16) if y.element_size() == 2 else y), f"replay {rep}"
+        for (c1, m1), (c2, m2) in zip(a[1], b[1]):
+            assert np.array_equal(c1.view(np.int32), c2.view(np.int32)) and np.array_equal(m1, m2), f"replay {rep}"
+        for t1, t2 in zip(a[2], b[2]):
+            assert np.array_equal(t1, t2), f"replay {rep}"
+    graph_ctx.close(); eager_ctx.close()
