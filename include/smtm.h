@@ -55,6 +55,11 @@ extern "C" {
 #define SMTM_SCORE_FP32   1   /* fp32 operands, fp32 vector arithmetic */
 #define SMTM_SCORE_MFMA   2   /* unit-normalised fp16 operands on the matrix cores, fp32 accumulate */
 
+/* how the forgetting of Sec. 6.1 acts on the frequency table */
+#define SMTM_FORGET_AT_SCORING 0   /* Eq. 5: Score = FT * 0.25^floor(TS/W), FT itself keeps the whole history */
+#define SMTM_FORGET_IN_PLACE   1   /* Sec. 6.1 text / Sec. 8.1: every W-th consecutive frame without class i
+                                      replaces FT_i by floor(FT_i / 4); Score = FT */
+
 typedef struct smtm_ctx smtm_ctx;
 
 typedef struct {
@@ -70,6 +75,7 @@ typedef struct {
     int32_t cl_num, cl_den;          /* confidence level of Eq. 6 as a fraction, 0 < cl_num <= cl_den (19/20) */
     int32_t init_count;              /* update count m every centre starts with (Eq. 7), >= 0 */
     int32_t score_path;              /* SMTM_SCORE_* */
+    int32_t forgetting;              /* SMTM_FORGET_* */
 } smtm_config;
 
 /* ---- life cycle ------------------------------------------------------------------------- */
@@ -199,6 +205,7 @@ int32_t smtm_read_stats(smtm_ctx* ctx, int32_t* stats_host, void* stream);
  * (i)  FT_j += 1 for the frame's class, TS_i = consecutive frames without class i (Sec. 6.1);
  * (ii) centres of class label[b] at exit points 1..stop_layer[b] move to the running mean
  *      (SC*m + SV)/(m+1) with the semantic vectors saved by smtm_encode (Eq. 7);
+ *      (with SMTM_FORGET_IN_PLACE the quartering is applied to FT_i as the frames go by instead);
  * (iii) Score_i = FT_i * 0.25^floor(TS_i/W) (Eq. 5, exact integers, exponent clamped at 15);
  * (iv) classes ordered by (Score desc, id asc); k = smallest size whose share of the total
  *      score reaches cl_num/cl_den (Eq. 6), clamped to [hot_min, hot_max]; the fast memory

@@ -280,6 +280,32 @@ void orc_tables_update(uint32_t *FT, uint32_t *TS, int n, const int32_t *label, 
 }
 
 /*
+ * Sec. 6.1, forgetting applied in place (the variant the text gives before Eq. 5 and Sec. 8.1 uses
+ * for fast-changing scenes): "we decay the memory ... every consecutive W frames".  Frame by frame:
+ * for every class other than the frame's own, TS_i += 1 and, each time TS_i reaches a multiple of
+ * W, the frequency entry is multiplied by 0.25; the frame's own class gets TS = 0, FT += 1.
+ * reading: the frequency entry is an integer count and 0.25 x is floor(x / 4).
+ */
+void orc_tables_update_inplace(uint32_t *FT, uint32_t *TS, int n, uint32_t W,
+                               const int32_t *label, int64_t batch)
+{
+    for (int64_t b = 0; b < batch; ++b) {
+        int32_t j = label[b];
+        for (int i = 0; i < n; ++i) {
+            if (i == j) continue;
+            if (TS[i] != UINT32_MAX) {
+                TS[i] += 1;
+                if (TS[i] % W == 0) FT[i] /= 4;
+            }
+        }
+        if (j >= 0 && j < n) {
+            TS[j] = 0;
+            if (FT[j] != UINT32_MAX) FT[j] += 1;
+        }
+    }
+}
+
+/*
  * Eq. 5 in exact integer arithmetic.  Score_i = FT_i * 0.25^floor(TS_i / W).
  * reading: the exponent q is clamped at 15 and every score is scaled by the
  * common factor 4^15, which changes neither the order nor the ratio of
@@ -319,14 +345,26 @@ static int cmp_entry(const void *a, const void *b)
     return (x->id > y->id) - (x->id < y->id);
 }
 
+int32_t orc_select_hot_mode(const uint32_t *FT, const uint32_t *TS, int n, uint32_t W, int inplace,
+                            uint32_t cl_num, uint32_t cl_den, int32_t k_min, int32_t k_max,
+                            int32_t *order, int32_t *k_unclamped);
+
 int32_t orc_select_hot(const uint32_t *FT, const uint32_t *TS, int n, uint32_t W,
                        uint32_t cl_num, uint32_t cl_den, int32_t k_min, int32_t k_max,
                        int32_t *order, int32_t *k_unclamped)
 {
+    return orc_select_hot_mode(FT, TS, n, W, 0, cl_num, cl_den, k_min, k_max, order, k_unclamped);
+}
+
+/* inplace != 0: the forgetting has already been applied to FT, so Score_i = FT_i. */
+int32_t orc_select_hot_mode(const uint32_t *FT, const uint32_t *TS, int n, uint32_t W, int inplace,
+                            uint32_t cl_num, uint32_t cl_den, int32_t k_min, int32_t k_max,
+                            int32_t *order, int32_t *k_unclamped)
+{
     orc_entry *e = (orc_entry *)malloc(sizeof(orc_entry) * (size_t)n);
     unsigned __int128 total = 0;
     for (int i = 0; i < n; ++i) {
-        e[i].score = orc_score_int(FT[i], TS[i], W);
+        e[i].score = inplace ? (uint64_t)FT[i] : orc_score_int(FT[i], TS[i], W);
         e[i].id = i;
         total += e[i].score;
     }

@@ -64,6 +64,11 @@ def lib():
         L.orc_compact.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp, ip, vp, vp, ip]
         L.orc_tables_update.restype = None
         L.orc_tables_update.argtypes = [vp, vp, C.c_int, vp, C.c_int64]
+        L.orc_tables_update_inplace.restype = None
+        L.orc_tables_update_inplace.argtypes = [vp, vp, C.c_int, C.c_uint32, vp, C.c_int64]
+        L.orc_select_hot_mode.restype = C.c_int32
+        L.orc_select_hot_mode.argtypes = [vp, vp, C.c_int, C.c_uint32, C.c_int, C.c_uint32, C.c_uint32,
+                                          C.c_int32, C.c_int32, vp, ip]
         L.orc_score_int.restype = C.c_uint64
         L.orc_score_int.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32]
         L.orc_score_real.restype = C.c_double
@@ -216,14 +221,21 @@ def tables_update(FT, TS, label):
     lib().orc_tables_update(_p(FT), _p(TS), FT.shape[0], _p(label), label.shape[0])
 
 
-def select_hot(FT, TS, W, cl_num, cl_den, k_min, k_max):
+def tables_update_inplace(FT, TS, W, label):
+    """Sec. 6.1 with the forgetting applied to the frequency table itself."""
+    assert FT.dtype == np.uint32 and TS.dtype == np.uint32
+    label = _c(label, np.int32)
+    lib().orc_tables_update_inplace(_p(FT), _p(TS), FT.shape[0], int(W), _p(label), label.shape[0])
+
+
+def select_hot(FT, TS, W, cl_num, cl_den, k_min, k_max, inplace=False):
     """Returns (order [n], k or -1, k before clamping)."""
     assert FT.dtype == np.uint32 and TS.dtype == np.uint32
     n = FT.shape[0]
     order = np.empty(n, np.int32)
     ku = C.c_int32()
-    k = lib().orc_select_hot(_p(FT), _p(TS), n, int(W), int(cl_num), int(cl_den),
-                             int(k_min), int(k_max), _p(order), C.byref(ku))
+    k = lib().orc_select_hot_mode(_p(FT), _p(TS), n, int(W), int(bool(inplace)), int(cl_num), int(cl_den),
+                                  int(k_min), int(k_max), _p(order), C.byref(ku))
     return order, int(k), int(ku.value)
 
 
@@ -261,7 +273,8 @@ class Memory:
     the frequency and time-stamp tables, and the fast-memory set Psi (policy order)."""
 
     def __init__(self, centres, hot_ids, *, tau, tiers=2, window=1024, cl=(19, 20),
-                 hot_min=2, hot_max=None, init_count=100):
+                 hot_min=2, hot_max=None, init_count=100, forgetting=0):
+        self.forgetting = int(forgetting)        # 0: at scoring time (Eq. 5); 1: in place (Sec. 6.1 text)
         self.SC = [np.ascontiguousarray(c, dtype=np.float64).copy() for c in centres]
         self.L = len(self.SC)
         self.n = self.SC[0].shape[0]
@@ -311,10 +324,13 @@ class Memory:
     def cache_update(self, label, stop_layer):
         """Sec. 6: tables, centres (Eq. 7), score (Eq. 5), fast-memory set and size (Eq. 6)."""
         label = np.asarray(label, np.int32); stop_layer = np.asarray(stop_layer, np.int32)
-        tables_update(self.FT, self.TS, label)
+        if self.forgetting:
+            tables_update_inplace(self.FT, self.TS, self.window, label)
+        else:
+            tables_update(self.FT, self.TS, label)
         centres_update(self.SC, self.m, self.SV, label, stop_layer)
         order, k, ku = select_hot(self.FT, self.TS, self.window, self.cl[0], self.cl[1],
-                                  self.hot_min, self.hot_max)
+                                  self.hot_min, self.hot_max, inplace=bool(self.forgetting))
         if k >= 0:
             self.hot_ids = order[:k].copy()
         return dict(order=order, k=k, k_unclamped=ku)

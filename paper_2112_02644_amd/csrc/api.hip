@@ -125,6 +125,8 @@ static int32_t validate_config(const smtm_config* c) {
     if (c->init_count < 0) return fail(nullptr, SMTM_ERR_INVALID_ARG, "init_count must be >= 0");
     if (c->score_path < SMTM_SCORE_AUTO || c->score_path > SMTM_SCORE_MFMA)
         return fail(nullptr, SMTM_ERR_INVALID_ARG, "score_path must be one of SMTM_SCORE_*");
+    if (c->forgetting != SMTM_FORGET_AT_SCORING && c->forgetting != SMTM_FORGET_IN_PLACE)
+        return fail(nullptr, SMTM_ERR_INVALID_ARG, "forgetting must be one of SMTM_FORGET_*");
     return SMTM_OK;
 }
 
@@ -531,7 +533,7 @@ int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* st
     const smtm_config& c = ctx->cfg;
     const int n = c.n_classes;
     launch_tables_update(label, batch, n, (uint32_t)c.window, ctx->FT, ctx->TS, ctx->cls_cnt, ctx->cls_last,
-                         ctx->score, ctx->score_total, ctx->below, st);
+                         ctx->score, ctx->score_total, ctx->below, c.forgetting, st);
     CentreTables tabs;
     for (int l = 0; l < SMTM_MAX_EXITS; ++l) {
         const bool on = l < c.n_exits;

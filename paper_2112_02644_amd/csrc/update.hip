@@ -29,10 +29,12 @@ __device__ __forceinline__ u128 shfl_xor_u128(u128 x, int off) {
 
 // Frequency / time-stamp tables for a whole batch, equal to taking the frames one by one:
 // FT_j += (appearances of j);  TS_j = (frames after j's last appearance) if j appeared,
-// else TS_j + batch.  Both saturate at 2^32 - 1.  Also leaves every class's score and the
+// else TS_j + batch.  Both saturate at 2^32 - 1.  With `inplace` the forgetting of Sec. 6.1 is applied
+// to the counts as the frames go by instead of at scoring time.  Also leaves every class's score and the
 // 128-bit total of the scores (total[0] low, total[1] high) and clears the policy counter.
 // Single block of 1024 threads.
 constexpr int kLdsClasses = 4096;
+constexpr int kLabelTile = 4096;
 
 __global__ __launch_bounds__(1024) void k_tables_update(const int32_t* __restrict__ label, int batch,
                                                         int n, uint32_t W, uint32_t* __restrict__ FT,
@@ -41,10 +43,11 @@ __global__ __launch_bounds__(1024) void k_tables_update(const int32_t* __restric
                                                         int32_t* __restrict__ cls_last,
                                                         uint64_t* __restrict__ score,
                                                         uint64_t* __restrict__ total,
-                                                        int32_t* __restrict__ below) {
+                                                        int32_t* __restrict__ below, int inplace) {
     __shared__ uint64_t red_lo[16], red_hi[16];
     __shared__ uint32_t l_cnt[kLdsClasses];
     __shared__ int32_t l_last[kLdsClasses];
+    __shared__ int32_t l_lab[kLabelTile];
     const int tid = threadIdx.x;
     const bool in_lds = n <= kLdsClasses;                // histogram in LDS when the classes fit, else in global memory
     for (int i = tid; i < n; i += 1024) {
@@ -60,6 +63,39 @@ __global__ __launch_bounds__(1024) void k_tables_update(const int32_t* __restric
     }
     __syncthreads();
     u128 part = 0;
+    if (inplace) {
+        // Forgetting applied to the frequency table itself (Sec. 6.1): thread = class, the batch's
+        // labels are walked in order; every W-th consecutive frame without the class quarters its count.
+        for (int c0 = 0; c0 < n; c0 += 1024) {           // uniform trip counts: the label tiles are shared
+            const int i = c0 + tid;
+            const bool valid = i < n;
+            uint32_t ft = valid ? FT[i] : 0u, ts = valid ? TS[i] : 0u;
+            uint32_t left = W - ts % W;                  // frames until TS reaches the next multiple of W
+            for (int b0 = 0; b0 < batch; b0 += kLabelTile) {
+                const int len = batch - b0 < kLabelTile ? batch - b0 : kLabelTile;
+                __syncthreads();
+                for (int b = tid; b < len; b += 1024) l_lab[b] = label[b0 + b];
+                __syncthreads();
+                if (valid) {
+                    for (int b = 0; b < len; ++b) {
+                        if (l_lab[b] == i) {
+                            ts = 0u; left = W;
+                            if (ft != 0xffffffffu) ++ft;
+                        } else if (ts != 0xffffffffu) {
+                            ++ts;
+                            if (--left == 0u) { ft >>= 2; left = W; }
+                        }
+                    }
+                }
+            }
+            if (valid) {
+                if (in_lds) cls_cnt[i] = l_cnt[i];       // the centre update reads the counts
+                FT[i] = ft; TS[i] = ts;
+                score[i] = (uint64_t)ft;                 // the decay is already in the count
+                part += ft;
+            }
+        }
+    } else
     for (int i = tid; i < n; i += 1024) {
         const uint32_t cnt_i = in_lds ? l_cnt[i] : cls_cnt[i];
         const int32_t last_i = in_lds ? l_last[i] : cls_last[i];
@@ -89,9 +125,9 @@ __global__ __launch_bounds__(1024) void k_tables_update(const int32_t* __restric
 
 void launch_tables_update(const int32_t* label, int batch, int n, uint32_t W, uint32_t* FT, uint32_t* TS,
                           uint32_t* cls_cnt, int32_t* cls_last, uint64_t* score, uint64_t* total,
-                          int32_t* below, hipStream_t st) {
+                          int32_t* below, int inplace, hipStream_t st) {
     hipLaunchKernelGGL(k_tables_update, dim3(1), dim3(1024), 0, st, label, batch, n, W, FT, TS, cls_cnt,
-                       cls_last, score, total, below);
+                       cls_last, score, total, below, inplace);
 }
 
 // Adaptive centres (Eq. 7), all exit points in one launch: block (j, l0) handles class j at

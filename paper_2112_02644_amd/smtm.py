@@ -30,7 +30,7 @@ class _Config(C.Structure):
                 ("max_batch", C.c_int32), ("hot_init", C.c_int32), ("hot_min", C.c_int32),
                 ("hot_max", C.c_int32), ("tiers", C.c_int32), ("tau", C.c_float),
                 ("window", C.c_int32), ("cl_num", C.c_int32), ("cl_den", C.c_int32),
-                ("init_count", C.c_int32), ("score_path", C.c_int32)]
+                ("init_count", C.c_int32), ("score_path", C.c_int32), ("forgetting", C.c_int32)]
 
 
 @dataclass
@@ -48,6 +48,7 @@ class SmtmConfig:
     cl_den: int = 20
     init_count: int = 100
     score_path: int = SCORE_AUTO
+    forgetting: int = 0              # 0: at scoring time (Eq. 5), 1: in place (Sec. 6.1 text)
 
     def to_c(self) -> _Config:
         c = _Config()
@@ -66,6 +67,7 @@ class SmtmConfig:
         c.cl_den = self.cl_den
         c.init_count = self.init_count
         c.score_path = self.score_path
+        c.forgetting = self.forgetting
         return c
 
 

@@ -70,12 +70,12 @@ class ParityReport:
 
 
 def make_ctx(w: Workload, cents, hot_ids, *, tau=None, tiers=None, score_path=SCORE_AUTO,
-             max_batch=None) -> Smtm:
+             max_batch=None, forgetting=0) -> Smtm:
     cfg = SmtmConfig(n_classes=w.n_classes, dims=w.dims, max_batch=max_batch or w.batch,
                      hot_init=len(hot_ids), hot_min=w.hot_min if w.hot_max else min(2, len(hot_ids)),
                      hot_max=w.hot_max or len(hot_ids), tiers=w.tiers if tiers is None else tiers,
                      tau=w.tau if tau is None else tau, window=w.window, init_count=w.init_count,
-                     score_path=score_path)
+                     score_path=score_path, forgetting=forgetting)
     ctx = Smtm(cfg)
     for l, c in enumerate(cents, start=1):
         ctx.memory_load(l, c.numpy())
@@ -84,11 +84,11 @@ def make_ctx(w: Workload, cents, hot_ids, *, tau=None, tiers=None, score_path=SC
     return ctx
 
 
-def make_oracle(w: Workload, cents, hot_ids, *, tau=None, tiers=None) -> O.Memory:
+def make_oracle(w: Workload, cents, hot_ids, *, tau=None, tiers=None, forgetting=0) -> O.Memory:
     return O.Memory([c.numpy() for c in cents], hot_ids, tau=w.tau if tau is None else tau,
                     tiers=w.tiers if tiers is None else tiers, window=w.window,
                     hot_min=w.hot_min if w.hot_max else min(2, len(hot_ids)),
-                    hot_max=w.hot_max or len(hot_ids), init_count=w.init_count)
+                    hot_max=w.hot_max or len(hot_ids), init_count=w.init_count, forgetting=forgetting)
 
 
 def _mean_abs(F: torch.Tensor, rows: np.ndarray) -> np.ndarray:

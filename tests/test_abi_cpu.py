@@ -42,8 +42,8 @@ def test_binding_covers_every_declared_symbol():
 
 
 def test_config_struct_matches_header_layout():
-    # 4 + 4 + 8*4 + 4*5 + 4 (float) + 4*5 = 84 bytes, all 4-byte fields in header order
-    assert C.sizeof(smtm._Config) == 84
+    # 4 + 4 + 8*4 + 4*5 + 4 (float) + 4*6 = 88 bytes, all 4-byte fields in header order
+    assert C.sizeof(smtm._Config) == 88
     fields = [f[0] for f in smtm._Config._fields_]
     header_fields = re.findall(r"^\s+(?:int32_t|float)\s+([a-z_, ]+?)(?:\[SMTM_MAX_EXITS\])?;", HEADER, flags=re.M)
     flat = [x.strip() for grp in header_fields for x in grp.split(",")]
@@ -56,7 +56,7 @@ BAD = [
     (dict(hot_init=1, hot_min=1), 1), (dict(hot_min=5, hot_init=4), 1), (dict(hot_max=3, hot_init=4), 1),
     (dict(hot_max=11), 1), (dict(tiers=3), 1), (dict(tau=-1.0), 1), (dict(tau=float("nan")), 1),
     (dict(window=0), 1), (dict(cl_num=0), 1), (dict(cl_num=21, cl_den=20), 1), (dict(init_count=-1), 1),
-    (dict(score_path=7), 1),
+    (dict(score_path=7), 1), (dict(forgetting=2), 1),
 ]
 
 

@@ -483,3 +483,78 @@ def test_step_captured_in_a_graph_replays_like_eager():
         for t1, t2 in zip(a[2], b[2]):
             assert np.array_equal(t1, t2), f"replay {rep}"
     graph_ctx.close(); eager_ctx.close()
+
+
+# ------------------------------------------------------------------ forgetting applied in place, per-frame cadence
+
+@pytest.mark.parametrize("window", [1, 7, 64, 5000])
+def test_cache_update_forgetting_in_place(window):
+    _say("in-place forgetting, W =", window)
+    rng = np.random.default_rng(window)
+    n = 120
+    w = dataclasses.replace(configs.ADAPTIVE, n_classes=n, exits=((16, 1, 1),), batch=900, hot=10, hot_min=4,
+                            hot_max=100, window=window)
+    cents = [torch.randn(n, 16)]
+    hot0 = np.arange(10, dtype=np.int32)
+    ctx = P.make_ctx(w, cents, hot0, forgetting=1)
+    mem = P.make_oracle(w, cents, hot0, forgetting=1)
+    for Bi in (900, 1, 333, 4500 if window == 5000 else 64):
+        if Bi > 900:
+            continue
+        ctx.begin_batch(Bi); mem.begin_batch(Bi)
+        zipf = np.minimum(rng.zipf(1.2, Bi) - 1, n - 1)
+        label = np.where(rng.random(Bi) < 0.15, -1, zipf).astype(np.int32)
+        P.check_cache_update(ctx, mem, label, np.zeros(Bi, np.int32))
+    # saturated tables stay saturated and stop decaying
+    ft = mem.FT.copy(); ts = mem.TS.copy()
+    ft[:3] = 2 ** 32 - 1; ts[3:6] = 2 ** 32 - 2
+    ctx.tables_import(ft, ts); mem.FT[:] = ft; mem.TS[:] = ts
+    ctx.begin_batch(5); mem.begin_batch(5)
+    P.check_cache_update(ctx, mem, np.array([0, 0, 7, -1, 1], np.int32), np.zeros(5, np.int32))
+    ctx.close()
+
+
+@pytest.mark.parametrize("forgetting", [0, 1])
+def test_frame_by_frame_cadence_equals_one_batch(forgetting):
+    # updating the memory after every frame (batches of one) leaves the same tables, order and size
+    # as one update with the whole batch
+    rng = np.random.default_rng(11 + forgetting)
+    n, B = 60, 150
+    w = dataclasses.replace(configs.ADAPTIVE, n_classes=n, exits=((8, 1, 1),), batch=B, hot=6, hot_min=3,
+                            hot_max=50, window=9)
+    cents = [torch.randn(n, 8)]
+    hot0 = np.arange(6, dtype=np.int32)
+    label = np.where(rng.random(B) < 0.1, -1, np.minimum(rng.zipf(1.3, B) - 1, n - 1)).astype(np.int32)
+    a = P.make_ctx(w, cents, hot0, forgetting=forgetting)
+    b = P.make_ctx(w, cents, hot0, forgetting=forgetting)
+    zero = torch.zeros(B, dtype=torch.int32, device=DEV)
+    lab_d = torch.from_numpy(label).to(DEV)
+    a.begin_batch(B)
+    a.cache_update(lab_d, zero, B)
+    for i in range(B):
+        b.begin_batch(1)
+        b.cache_update(lab_d[i:i + 1].clone(), zero[:1], 1)
+    torch.cuda.synchronize()
+    ta, tb = a.tables_export(), b.tables_export()
+    for x, y in zip(ta, tb):
+        assert np.array_equal(x, y)
+    a.close(); b.close()
+
+
+def test_adaptive_stream_short_forgetting_in_place():
+    w = dataclasses.replace(configs.ADAPTIVE, total_frames=512 * 6, drift_every=1024, window=256)
+    cents = streams.centroids(w)
+    ls = streams.labels(w, w.batch * 6)
+    ctx = P.make_ctx(w, cents, ls.initial_hot, forgetting=1)
+    mem = P.make_oracle(w, cents, ls.initial_hot, forgetting=1)
+    rep = P.ParityReport()
+    for b in range(6):
+        fm = streams.batch_feature_maps(w, cents, ls, b, DEV)
+        P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), check_sims=False, report=rep,
+                      fused="lookup_exit")
+        truth = ls.label[b * w.batch:(b + 1) * w.batch]
+        label = np.where(mem.exit_layer > 0, mem.label, truth).astype(np.int32)
+        P.check_cache_update(ctx, mem, label, mem.exit_layer.astype(np.int32))
+        rep.hot_sizes.append(len(mem.hot_ids))
+    _say("  hot sizes", rep.hot_sizes, "exits", rep.exit_hist)
+    ctx.close()

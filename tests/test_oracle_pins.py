@@ -576,3 +576,72 @@ def test_memory_stage_on_generated_tiny_workload_recovers_classes():
     assert set(np.unique(out["decision"])) == {0, 1, 2}
     assert set(out["label"][out["decision"] == 1]) <= set(ls.initial_hot.tolist())
     assert np.array_equal(out["label"][out["decision"] == 2], ls.label[out["decision"] == 2])
+
+
+# ------------------------------------------------------------------ forgetting applied in place (Sec. 6.1 text)
+
+def _inplace_brute(FT, TS, W, label):
+    FT = [int(x) for x in FT]; TS = [int(x) for x in TS]
+    for j in label:
+        for i in range(len(FT)):
+            if i == j:
+                continue
+            TS[i] += 1
+            if TS[i] % W == 0:
+                FT[i] = FT[i] // 4
+        if j >= 0:
+            TS[j] = 0
+            FT[j] += 1
+    return FT, TS
+
+
+def test_inplace_forgetting_matches_python_brute_force():
+    for trial in range(100):
+        n = int(rng.integers(2, 7)); W = int(rng.integers(1, 9)); B = int(rng.integers(1, 40))
+        FT = rng.integers(0, 300, n).astype(np.uint32); TS = rng.integers(0, 30, n).astype(np.uint32)
+        label = rng.integers(-1, n, B).astype(np.int32)
+        want = _inplace_brute(FT, TS, W, label.tolist())
+        O.tables_update_inplace(FT, TS, W, label)
+        assert FT.tolist() == want[0] and TS.tolist() == want[1]
+
+
+def test_inplace_forgetting_hand_example_and_relation_to_eq5():
+    # class 0 seen 64 times, then 10 frames of class 1 with W = 4: TS_0 = 10, two decays -> 64/16 = 4
+    FT = np.array([64, 0], np.uint32); TS = np.zeros(2, np.uint32)
+    O.tables_update_inplace(FT, TS, 4, np.ones(10, np.int32))
+    assert FT.tolist() == [4, 10] and TS.tolist() == [10, 0]
+    # while a class stays away, the in-place value is the floor of Eq. 5's score ...
+    assert FT[0] == math.floor(O.score_real(64, 10, 4))
+    # ... but when it comes back the decayed history stays forgotten (Eq. 5 would give 65 again)
+    O.tables_update_inplace(FT, TS, 4, np.zeros(1, np.int32))
+    assert FT[0] == 5 and TS[0] == 0
+    FT2 = np.array([64, 0], np.uint32); TS2 = np.zeros(2, np.uint32)
+    O.tables_update(FT2, TS2, np.array([1] * 10 + [0], np.int32))
+    assert O.score_int(int(FT2[0]), int(TS2[0]), 4) == 65 * 4 ** 15
+
+
+def test_frame_by_frame_cadence_equals_one_batch_for_both_forgetting_modes():
+    n, W = 9, 5
+    label = rng.integers(-1, n, 137).astype(np.int32)
+    for inplace in (False, True):
+        FT = rng.integers(0, 50, n).astype(np.uint32); TS = rng.integers(0, 20, n).astype(np.uint32)
+        FTa, TSa, FTb, TSb = FT.copy(), TS.copy(), FT.copy(), TS.copy()
+        if inplace:
+            O.tables_update_inplace(FTa, TSa, W, label)
+            for x in label:
+                O.tables_update_inplace(FTb, TSb, W, np.array([x], np.int32))
+        else:
+            O.tables_update(FTa, TSa, label)
+            for x in label:
+                O.tables_update(FTb, TSb, np.array([x], np.int32))
+        assert np.array_equal(FTa, FTb) and np.array_equal(TSa, TSb)
+        a = O.select_hot(FTa, TSa, W, 19, 20, 2, n, inplace=inplace)
+        b = O.select_hot(FTb, TSb, W, 19, 20, 2, n, inplace=inplace)
+        assert a[0].tolist() == b[0].tolist() and a[1:] == b[1:]
+
+
+def test_select_hot_inplace_scores_are_the_frequencies():
+    FT = np.array([3, 9, 9, 0, 1], np.uint32); TS = np.array([0, 500, 0, 0, 7], np.uint32)
+    order, k, ku = O.select_hot(FT, TS, 10, 19, 20, 1, 5, inplace=True)
+    assert order.tolist() == [1, 2, 0, 4, 3]            # TS plays no part any more; ties by id
+    assert ku == 3                                       # (9+9+3)/22 = 0.9545 >= 0.95, (9+9)/22 is not
