@@ -97,6 +97,18 @@ int32_t smtm_version(void);
  * copied (the host buffer must stay valid until the stream has passed this call).  Centres
  * need not be unit length.  Resets that exit point's update counts to init_count. */
 int32_t smtm_memory_load(smtm_ctx* ctx, int32_t exit, const float* centres_host, void* stream);
+/* Warm-up (Sec. 5, Sec. 6.3): centres initialised as the average of the semantic vectors of labelled
+ * training frames, update counts as the number of samples per class.
+ *   smtm_warmup_begin  sets every centre to 0 and every update count to 0.
+ *   smtm_warmup_batch  adds one labelled batch: call smtm_begin_batch, then smtm_encode at every exit
+ *                      point (all frames live, no lookup), then this with label[b] (device int32
+ *                      [batch], class of frame b or -1 to skip it).  Centres move to the running mean
+ *                      (SC*m + sum of SV)/(m + count), which after the last batch is the class mean.
+ * Classes that never appear keep the zero vector (similarity 0 to everything).  Nothing else of the
+ * memory (tables, fast-memory set) is touched.  Errors: STATE when an exit point of the batch has not
+ * been encoded (or has been looked up), SHAPE when batch differs from the batch begun. */
+int32_t smtm_warmup_begin(smtm_ctx* ctx, void* stream);
+int32_t smtm_warmup_batch(smtm_ctx* ctx, const int32_t* label, int32_t batch, void* stream);
 /* Sets the fast memory Psi to k distinct class ids (host), hot_min <= k <= hot_max. */
 int32_t smtm_hot_set(smtm_ctx* ctx, const int32_t* class_ids_host, int32_t k, void* stream);
 /* Copies one exit point's centres ([n, C_l] fp32) and update counts ([n] uint32) to host

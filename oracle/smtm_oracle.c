@@ -428,6 +428,32 @@ void orc_centres_update(double **SC, uint32_t **m, const int32_t *dims, int L, i
     }
 }
 
+/*
+ * Sec. 5 / Sec. 6.3, warm-up: the semantic centre of a class is the average of the semantic
+ * vectors of its training samples, and its update count m is the number of those samples.
+ *
+ *   SV     [N, C] semantic vectors of the training frames (one exit point)
+ *   label  [N] class of each frame (frames with label outside 0..n-1 are ignored)
+ *   SC     out [n, C]; a class without samples gets the zero vector and m = 0
+ */
+void orc_warmup_centres(const double *SV, const int32_t *label, int64_t N, int n, int C,
+                        double *SC, uint32_t *m)
+{
+    for (int j = 0; j < n; ++j) {
+        m[j] = 0;
+        for (int c = 0; c < C; ++c) SC[(int64_t)j * C + c] = 0.0;
+    }
+    for (int64_t b = 0; b < N; ++b) {
+        int32_t j = label[b];
+        if (j < 0 || j >= n) continue;
+        m[j] += 1;
+        for (int c = 0; c < C; ++c) SC[(int64_t)j * C + c] += SV[b * C + c];
+    }
+    for (int j = 0; j < n; ++j)
+        if (m[j] > 0)
+            for (int c = 0; c < C; ++c) SC[(int64_t)j * C + c] /= (double)m[j];
+}
+
 /* Eq. 2 (single-layer separability), for diagnostics only. */
 double orc_sep(double s_H, double s_SH)
 {

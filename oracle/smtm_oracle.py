@@ -80,6 +80,8 @@ def lib():
         L.orc_p_of_a.argtypes = [vp, vp, C.c_int, C.c_uint32, vp, C.c_int]
         L.orc_centres_update.restype = None
         L.orc_centres_update.argtypes = [vp, vp, vp, C.c_int, C.c_int, vp, vp, vp, C.c_int64]
+        L.orc_warmup_centres.restype = None
+        L.orc_warmup_centres.argtypes = [vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp]
         L.orc_sep.restype = C.c_double
         L.orc_sep.argtypes = [C.c_double, C.c_double]
         _lib = L
@@ -260,6 +262,16 @@ def centres_update(SC_list, m_list, SV_list, label, stop_layer):
     m_p = PP(*[m.ctypes.data for m in m_list])
     sv_p = PP(*[sv.ctypes.data for sv in SV_list])
     lib().orc_centres_update(sc_p, m_p, _p(dims), L, n, sv_p, _p(label), _p(stop_layer), batch)
+
+
+def warmup_centres(SV, label, n):
+    """Class means of the training frames' semantic vectors: returns (SC [n,C] float64, m [n] uint32)."""
+    SV = _c(SV, np.float64); label = _c(label, np.int32)
+    N, Cc = SV.shape
+    assert label.shape[0] == N
+    SC = np.empty((n, Cc), np.float64); m = np.empty(n, np.uint32)
+    lib().orc_warmup_centres(_p(SV), _p(label), N, int(n), Cc, _p(SC), _p(m))
+    return SC, m
 
 
 def sep(s_H, s_SH) -> float:

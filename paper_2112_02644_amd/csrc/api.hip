@@ -56,6 +56,7 @@ struct smtm_ctx {
     uint64_t* score_total;                       // [2] 128-bit sum of the scores
     int32_t* below;                              // [1] classes whose prefix share is below the confidence level
     int32_t* order;
+    int32_t* all_exits;                          // [max_batch] filled with L: "stopped at the last exit point"
     // pinned staging for small host -> device copies
     void* pinned;
     size_t pinned_bytes;
@@ -204,6 +205,7 @@ int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
     CREATE_TRY(dev_alloc(ctx, &ctx->order, (size_t)n));
     CREATE_TRY(dev_alloc(ctx, &ctx->score_total, (size_t)2));
     CREATE_TRY(dev_alloc(ctx, &ctx->below, (size_t)1));
+    CREATE_TRY(dev_alloc(ctx, &ctx->all_exits, (size_t)B));
     ctx->pinned_bytes = sizeof(int32_t) * (size_t)cfg->hot_max;
     CREATE_TRY(hipHostMalloc(&ctx->pinned, ctx->pinned_bytes, hipHostMallocDefault));
 
@@ -215,6 +217,7 @@ int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
         CREATE_TRY(hipMemset(ctx->sv[l], 0, sizeof(float) * (size_t)B * cfg->dims[l]));
         launch_fill_u32(ctx->mcount[l], (uint32_t)cfg->init_count, n, nullptr);
     }
+    launch_fill_u32(reinterpret_cast<uint32_t*>(ctx->all_exits), (uint32_t)L, B, nullptr);
     CREATE_TRY(hipMemset(ctx->FT, 0, sizeof(uint32_t) * (size_t)n));
     CREATE_TRY(hipMemset(ctx->TS, 0, sizeof(uint32_t) * (size_t)n));
     CREATE_TRY(hipMemset(ctx->counts, 0, sizeof(Counts)));
@@ -524,6 +527,51 @@ int32_t smtm_read_stats(smtm_ctx* ctx, int32_t* stats_host, void* stream) {
     return SMTM_OK;
 }
 
+static CentreTables centre_tables(const smtm_ctx* ctx) {
+    CentreTables tabs;
+    for (int l = 0; l < SMTM_MAX_EXITS; ++l) {
+        const bool on = l < ctx->cfg.n_exits;
+        tabs.centres[l] = on ? ctx->centres[l] : nullptr;
+        tabs.mcount[l] = on ? ctx->mcount[l] : nullptr;
+        tabs.cinv[l] = on ? ctx->cinv[l] : nullptr;
+        tabs.chat[l] = on ? ctx->chat[l] : nullptr;
+        tabs.sv[l] = on ? ctx->sv[l] : nullptr;
+        tabs.C[l] = on ? ctx->cfg.dims[l] : 0;
+        tabs.Cp[l] = on ? ctx->Cp[l] : 0;
+    }
+    return tabs;
+}
+
+int32_t smtm_warmup_begin(smtm_ctx* ctx, void* stream) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int n = ctx->cfg.n_classes;
+    for (int l = 0; l < ctx->cfg.n_exits; ++l) {
+        launch_fill_u32(reinterpret_cast<uint32_t*>(ctx->centres[l]), 0u, n * ctx->cfg.dims[l], st);
+        launch_fill_u32(ctx->mcount[l], 0u, n, st);
+        launch_centre_prepare(ctx->centres[l], n, ctx->cfg.dims[l], ctx->cinv[l], ctx->chat[l], ctx->Cp[l], 0, ctx->n_pad, st);
+    }
+    return check_launch(ctx, "smtm_warmup_begin");
+}
+
+int32_t smtm_warmup_batch(smtm_ctx* ctx, const int32_t* label, int32_t batch, void* stream) {
+    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (!label) return fail(ctx, SMTM_ERR_INVALID_ARG, "label is NULL");
+    if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");
+    if (batch != ctx->batch) return fail(ctx, SMTM_ERR_SHAPE, "batch %d differs from the batch begun (%d)", batch, ctx->batch);
+    for (int l = 0; l < ctx->cfg.n_exits; ++l)
+        if (ctx->stage_done[l] != 1)
+            return fail(ctx, SMTM_ERR_STATE, "smtm_warmup_batch needs smtm_encode (and nothing else) at every exit point of this batch; exit point %d is missing", l + 1);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int n = ctx->cfg.n_classes;
+    launch_class_count(label, batch, n, ctx->cls_cnt, st);
+    launch_centres_update(centre_tables(ctx), ctx->cfg.n_exits, n, label, ctx->all_exits, batch, ctx->cls_cnt, st);
+    int32_t rc = check_launch(ctx, "smtm_warmup_batch");
+    if (rc) return rc;
+    for (int l = 0; l < ctx->cfg.n_exits; ++l) ctx->stage_done[l] = 3;     // the batch has been used
+    return SMTM_OK;
+}
+
 int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* stop_layer, int32_t batch, void* stream) {
     if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
     if (!label || !stop_layer) return fail(ctx, SMTM_ERR_INVALID_ARG, "label / stop_layer is NULL");
@@ -534,18 +582,7 @@ int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* st
     const int n = c.n_classes;
     launch_tables_update(label, batch, n, (uint32_t)c.window, ctx->FT, ctx->TS, ctx->cls_cnt, ctx->cls_last,
                          ctx->score, ctx->score_total, ctx->below, c.forgetting, st);
-    CentreTables tabs;
-    for (int l = 0; l < SMTM_MAX_EXITS; ++l) {
-        const bool on = l < c.n_exits;
-        tabs.centres[l] = on ? ctx->centres[l] : nullptr;
-        tabs.mcount[l] = on ? ctx->mcount[l] : nullptr;
-        tabs.cinv[l] = on ? ctx->cinv[l] : nullptr;
-        tabs.chat[l] = on ? ctx->chat[l] : nullptr;
-        tabs.sv[l] = on ? ctx->sv[l] : nullptr;
-        tabs.C[l] = on ? c.dims[l] : 0;
-        tabs.Cp[l] = on ? ctx->Cp[l] : 0;
-    }
-    launch_centres_update(tabs, c.n_exits, n, label, stop_layer, batch, ctx->cls_cnt, st);
+    launch_centres_update(centre_tables(ctx), c.n_exits, n, label, stop_layer, batch, ctx->cls_cnt, st);
     launch_policy(ctx->score, ctx->score_total, n, (uint32_t)c.cl_num, (uint32_t)c.cl_den, c.hot_min, c.hot_max,
                   ctx->order, ctx->below, ctx->hot_ids, ctx->in_hot, ctx->counts, st);
     return check_launch(ctx, "smtm_cache_update");

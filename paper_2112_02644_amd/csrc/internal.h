@@ -85,6 +85,7 @@ struct CentreTables {                     // per exit point, passed by value to 
 void launch_tables_update(const int32_t* label, int batch, int n, uint32_t W, uint32_t* FT, uint32_t* TS,
                           uint32_t* cls_cnt, int32_t* cls_last, uint64_t* score, uint64_t* total,
                           int32_t* below, int inplace, hipStream_t st);
+void launch_class_count(const int32_t* label, int batch, int n, uint32_t* cls_cnt, hipStream_t st);
 void launch_centres_update(const CentreTables& tabs, int n_exits, int n, const int32_t* label,
                            const int32_t* stop_layer, int batch, const uint32_t* cls_cnt, hipStream_t st);
 void launch_policy(const uint64_t* score, const uint64_t* total, int n, uint32_t cl_num, uint32_t cl_den,

@@ -130,6 +130,21 @@ void launch_tables_update(const int32_t* label, int batch, int n, uint32_t W, ui
                        cls_last, score, total, below, inplace);
 }
 
+// Appearances of every class in a batch of labels (nothing else is touched).  Single block.
+__global__ __launch_bounds__(1024) void k_class_count(const int32_t* __restrict__ label, int batch, int n,
+                                                      uint32_t* __restrict__ cls_cnt) {
+    for (int i = threadIdx.x; i < n; i += 1024) cls_cnt[i] = 0;
+    __syncthreads();
+    for (int b = threadIdx.x; b < batch; b += 1024) {
+        const int j = label[b];
+        if (j >= 0 && j < n) atomicAdd(&cls_cnt[j], 1u);
+    }
+}
+
+void launch_class_count(const int32_t* label, int batch, int n, uint32_t* cls_cnt, hipStream_t st) {
+    hipLaunchKernelGGL(k_class_count, dim3(1), dim3(1024), 0, st, label, batch, n, cls_cnt);
+}
+
 // Adaptive centres (Eq. 7), all exit points in one launch: block (j, l0) handles class j at
 // exit point l0.  Taking the frames of class j one by one gives the running mean
 // (m*SC + sum of their SV) / (m + count); the sum is taken in ascending frame order, so the

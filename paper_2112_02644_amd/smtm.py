@@ -88,6 +88,8 @@ def load_library():
         "smtm_version": [],
         "smtm_memory_load": [vp, i32, vp, vp],
         "smtm_hot_set": [vp, vp, i32, vp],
+        "smtm_warmup_begin": [vp, vp],
+        "smtm_warmup_batch": [vp, vp, i32, vp],
         "smtm_memory_export": [vp, i32, vp, vp, vp],
         "smtm_tables_export": [vp, vp, vp, vp, vp, vp],
         "smtm_tables_import": [vp, vp, vp, vp],
@@ -178,6 +180,12 @@ class Smtm:
     # -- memory
     def memory_load(self, exit: int, centres_host, stream=None):
         self._ck(self.lib.smtm_memory_load(self._h, exit, _ptr(centres_host), self._st(stream)))
+
+    def warmup_begin(self, stream=None):
+        self._ck(self.lib.smtm_warmup_begin(self._h, self._st(stream)))
+
+    def warmup_batch(self, label, batch: int, stream=None):
+        self._ck(self.lib.smtm_warmup_batch(self._h, _ptr(label), batch, self._st(stream)))
 
     def hot_set(self, class_ids_host, stream=None):
         import numpy as np

@@ -558,3 +558,58 @@ def test_adaptive_stream_short_forgetting_in_place():
         rep.hot_sizes.append(len(mem.hot_ids))
     _say("  hot sizes", rep.hot_sizes, "exits", rep.exit_hist)
     ctx.close()
+
+
+# ------------------------------------------------------------------ warm-up of the centres from labelled frames
+
+def test_warmup_from_a_labelled_stream_then_inference():
+    # a labelled "training" stream (the same generator, its own seed salt through the batch index) builds the
+    # centres as class means; an inference batch then runs on the warmed-up memory on both sides
+    w = dataclasses.replace(configs.RESNET18, batch=192, n_classes=60, hot=12, sigma=0.4,
+                            exits=((64, 28, 28), (128, 14, 14), (256, 7, 7)))
+    cents = streams.centroids(w)
+    n_train = 3
+    ls = streams.labels(w, w.batch * (n_train + 1))
+    ctx = P.make_ctx(w, [torch.zeros_like(c) for c in cents], ls.initial_hot)
+    ctx.warmup_begin()
+    sv_all = [[] for _ in w.exits]; lab_all = []
+    for b in range(n_train):
+        Bi = w.batch if b < n_train - 1 else 100          # a short last batch
+        fm = [f[:Bi].contiguous() for f in streams.batch_feature_maps(w, cents, ls, b, DEV)]
+        lab = ls.label[b * w.batch: b * w.batch + Bi].astype(np.int32)
+        ctx.begin_batch(Bi)
+        for l in range(1, w.n_exits + 1):
+            ctx.encode(l, fm[l - 1])
+            sv_all[l - 1].append(O.encode(fm[l - 1].cpu().numpy()))
+        ctx.warmup_batch(torch.from_numpy(lab).to(DEV), Bi)
+        lab_all.append(lab)
+    torch.cuda.synchronize()
+    lab_all = np.concatenate(lab_all)
+    ref = [O.warmup_centres(np.concatenate(s), lab_all, w.n_classes) for s in sv_all]
+    for l in range(1, w.n_exits + 1):
+        cg, mg = ctx.memory_export(l)
+        SC, m = ref[l - 1]
+        assert np.array_equal(mg, m)
+        scale = np.maximum(np.abs(SC).max(axis=1, keepdims=True), 1e-30)
+        assert (np.abs(cg - SC) / scale).max() <= 1e-5
+        assert np.all(cg[m == 0] == 0)
+        # warmed-up centres point at the generating centroids
+        seen = m >= 3
+        cos = (cg[seen] * cents[l - 1].numpy()[seen]).sum(1) / np.linalg.norm(cg[seen], axis=1)
+        assert cos.min() > 0.8
+    # call-order errors
+    with pytest.raises(SmtmError) as e:
+        ctx.warmup_batch(torch.zeros(100, dtype=torch.int32, device=DEV), 100)
+    assert e.value.code == 3                                # the same batch cannot be added twice
+    # inference on the warmed-up memory, both sides
+    mem = P.make_oracle(w, [torch.from_numpy(SC) for SC, _ in ref], ls.initial_hot)
+    for l in range(w.n_exits):
+        mem.m[l][:] = ref[l][1]
+    fm = streams.batch_feature_maps(w, cents, ls, n_train, DEV)
+    rep = P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w))
+    _say("  after warm-up: exits", rep.exit_hist, "flips", rep.in_band_flips)
+    assert rep.exit_hist[0] < w.batch // 2                  # most frames are recognised early
+    truth = ls.label[n_train * w.batch:(n_train + 1) * w.batch]
+    label = np.where(mem.exit_layer > 0, mem.label, truth).astype(np.int32)
+    P.check_cache_update(ctx, mem, label, mem.exit_layer.astype(np.int32))
+    ctx.close()

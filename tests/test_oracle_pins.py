@@ -645,3 +645,29 @@ def test_select_hot_inplace_scores_are_the_frequencies():
     order, k, ku = O.select_hot(FT, TS, 10, 19, 20, 1, 5, inplace=True)
     assert order.tolist() == [1, 2, 0, 4, 3]            # TS plays no part any more; ties by id
     assert ku == 3                                       # (9+9+3)/22 = 0.9545 >= 0.95, (9+9)/22 is not
+
+
+# ------------------------------------------------------------------ warm-up (Sec. 5, Sec. 6.3)
+
+def test_warmup_centres_are_class_means():
+    n, C, N = 7, 5, 60
+    SV = rng.standard_normal((N, C)); label = rng.integers(-1, n, N).astype(np.int32)
+    label[label == 3] = 2                                  # class 3 has no samples
+    SC, m = O.warmup_centres(SV, label, n)
+    for j in range(n):
+        sel = label == j
+        assert m[j] == sel.sum()
+        want = SV[sel].mean(axis=0) if sel.any() else np.zeros(C)
+        assert np.allclose(SC[j], want, rtol=1e-14, atol=1e-16)
+    assert np.all(SC[3] == 0) and m[3] == 0
+
+
+def test_warmup_equals_eq7_started_from_count_zero():
+    # the running mean of Eq. 7 with m = 0 at the start reaches the same centres
+    n, C, N = 4, 3, 25
+    SV = rng.standard_normal((N, C)); label = rng.integers(0, n, N).astype(np.int32)
+    SC, m = O.warmup_centres(SV, label, n)
+    SC2 = [np.full((n, C), 123.0)]; m2 = [np.zeros(n, np.uint32)]
+    O.centres_update(SC2, m2, [SV], label, np.ones(N, np.int32))
+    seen = m > 0
+    assert np.allclose(SC2[0][seen], SC[seen], rtol=1e-13) and np.array_equal(m2[0], m)
