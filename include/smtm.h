@@ -155,6 +155,15 @@ int32_t smtm_encode(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype
 int32_t smtm_lookup(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id,
                     float* sims_out, void* stream);
 
+/* Diagnostic, not on the decision path: single-layer separability (Eq. 2) of the live frames,
+ * sep = (s_H - s_SH) / s_SH with s_H, s_SH the highest and second-highest similarity of THIS exit
+ * point over the fast memory (tier 1) and over the global memory (tier 2).
+ *   sims     device [batch, n] fp32: the sims_out of smtm_lookup for this exit point
+ *   sep_out  device [batch, 2 tiers] fp32; +inf where s_SH <= 0 < s_H, -inf where s_H <= 0 or the
+ *            tier has fewer than two entries
+ * To be called after smtm_lookup and before smtm_exit_compact of the exit point (else SMTM_ERR_STATE). */
+int32_t smtm_separability(smtm_ctx* ctx, int32_t exit, const float* sims, float* sep_out, void* stream);
+
 /* 3. Exit and compact (Sec. 1 "skip the rest layers", Sec. 5 last paragraph): stable partition
  * of the live frames into those released at this exit point and those that continue.
  * Device outputs (any may be NULL), lists in ascending original frame id:

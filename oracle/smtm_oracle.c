@@ -459,3 +459,18 @@ double orc_sep(double s_H, double s_SH)
 {
     return (s_H - s_SH) / s_SH;
 }
+
+/*
+ * Eq. 2 for one frame over a set of classes: s_H and s_SH are the highest and second-highest
+ * similarity of one exit point.  reading (as for Eq. 4): +inf where s_SH <= 0 < s_H, -inf where
+ * s_H <= 0 or the set has fewer than two members.
+ */
+double orc_separability(const double *s, const int32_t *ids, int count)
+{
+    double h, sh;
+    int32_t id;
+    orc_top2(s, ids, count, &h, &id, &sh);
+    if (!(h > 0.0) || sh == -INFINITY) return -INFINITY;
+    if (!(sh > 0.0)) return INFINITY;
+    return orc_sep(h, sh);
+}

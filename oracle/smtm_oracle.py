@@ -82,6 +82,8 @@ def lib():
         L.orc_centres_update.argtypes = [vp, vp, vp, C.c_int, C.c_int, vp, vp, vp, C.c_int64]
         L.orc_warmup_centres.restype = None
         L.orc_warmup_centres.argtypes = [vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp]
+        L.orc_separability.restype = C.c_double
+        L.orc_separability.argtypes = [vp, vp, C.c_int]
         L.orc_sep.restype = C.c_double
         L.orc_sep.argtypes = [C.c_double, C.c_double]
         _lib = L
@@ -272,6 +274,14 @@ def warmup_centres(SV, label, n):
     SC = np.empty((n, Cc), np.float64); m = np.empty(n, np.uint32)
     lib().orc_warmup_centres(_p(SV), _p(label), N, int(n), Cc, _p(SC), _p(m))
     return SC, m
+
+
+def separability(s, ids=None) -> float:
+    """Eq. 2 for one frame's similarities over a set of classes (None = all)."""
+    s = _c(s, np.float64)
+    if ids is not None:
+        ids = _c(ids, np.int32)
+    return float(lib().orc_separability(_p(s), _p(ids), s.shape[0] if ids is None else ids.shape[0]))
 
 
 def sep(s_H, s_SH) -> float:

@@ -438,6 +438,17 @@ int32_t smtm_lookup(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id
     return SMTM_OK;
 }
 
+int32_t smtm_separability(smtm_ctx* ctx, int32_t exit, const float* sims, float* sep_out, void* stream) {
+    int32_t rc = check_ctx_exit(ctx, exit);
+    if (rc) return rc;
+    if (!sims || !sep_out) return fail(ctx, SMTM_ERR_INVALID_ARG, "sims / sep_out is NULL");
+    if (ctx->batch == 0 || ctx->stage_done[exit - 1] != 2)
+        return fail(ctx, SMTM_ERR_STATE, "smtm_separability(%d) goes between smtm_lookup(%d) and smtm_exit_compact(%d)", exit, exit, exit);
+    launch_separability(sims, ctx->counts, ctx->batch, ctx->cfg.n_classes, ctx->in_hot, sep_out,
+                        static_cast<hipStream_t>(stream));
+    return check_launch(ctx, "smtm_separability");
+}
+
 int32_t smtm_exit_compact(smtm_ctx* ctx, int32_t exit, int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
                           int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev, const void* fmap_in,
                           const int32_t* row_ids, void* fmap_out, int64_t row_bytes, void* stream) {

@@ -59,6 +59,9 @@ void launch_top2_decide(const float* SA, const int32_t* frame_ids, const Counts*
                         int32_t* label, float* top_val, int32_t* top_id, float* top_val_user,
                         int32_t* top_id_user, hipStream_t st);
 
+void launch_separability(const float* sims, const Counts* counts, int max_rows, int n, const uint8_t* in_hot,
+                         float* sep_out, hipStream_t st);
+
 // ---- compact.hip ------------------------------------------------------------------------
 void launch_begin_batch(float* SA, int n, int batch, int32_t* live, int32_t* res_layer,
                         int32_t* res_label, int32_t* res_tier, Counts* counts, hipStream_t st);

@@ -446,6 +446,52 @@ __global__ __launch_bounds__(256) void k_top2_decide(
     }
 }
 
+// Single-layer separability (Eq. 2): sep = (s_H - s_SH) / s_SH over one exit point's similarities,
+// per tier.  A diagnostic, not on the decision path.  One wavefront per live slot.
+// +inf where s_SH <= 0 < s_H, -inf where s_H <= 0 or the tier has fewer than two entries.
+__global__ __launch_bounds__(256) void k_separability(const float* __restrict__ sims,
+                                                      const Counts* __restrict__ counts, int max_rows, int n,
+                                                      const uint8_t* __restrict__ in_hot,
+                                                      float* __restrict__ sep_out) {
+    const int lane = threadIdx.x & 63;
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    const int n_waves = gridDim.x * 4;
+    const float ninf = -__builtin_inff();
+    for (int slot = blockIdx.x * 4 + (threadIdx.x >> 6); slot < n_live; slot += n_waves) {
+        const float* row = sims + (int64_t)slot * n;
+        Top2 hot = {ninf, -1, ninf}, all = {ninf, -1, ninf};
+        for (int j = lane; j < n; j += 64) {
+            const float x = row[j];
+            top2_push(all, x, j);
+            if (in_hot[j]) top2_push(hot, x, j);
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            float v1 = __shfl_xor(all.v1, off, 64); int id1 = __shfl_xor(all.id1, off, 64);
+            float v2 = __shfl_xor(all.v2, off, 64);
+            top2_merge(all, v1, id1, v2);
+            v1 = __shfl_xor(hot.v1, off, 64); id1 = __shfl_xor(hot.id1, off, 64);
+            v2 = __shfl_xor(hot.v2, off, 64);
+            top2_merge(hot, v1, id1, v2);
+        }
+        if (lane < 2) {
+            const Top2 t = lane == 0 ? hot : all;
+            float sep;
+            if (!(t.v1 > 0.f) || t.v2 == ninf) sep = ninf;
+            else if (!(t.v2 > 0.f)) sep = __builtin_inff();
+            else sep = (t.v1 - t.v2) / t.v2;
+            sep_out[slot * 2 + lane] = sep;
+        }
+    }
+}
+
+void launch_separability(const float* sims, const Counts* counts, int max_rows, int n, const uint8_t* in_hot,
+                         float* sep_out, hipStream_t st) {
+    int grid = (max_rows + 3) / 4;
+    if (grid > 2048) grid = 2048;
+    hipLaunchKernelGGL(k_separability, grid, dim3(256), 0, st, sims, counts, max_rows, n, in_hot, sep_out);
+}
+
 void launch_top2_decide(const float* SA, const int32_t* frame_ids, const Counts* counts, int max_rows,
                         int n, const uint8_t* in_hot, int tiers, float tau, int32_t* decision,
                         int32_t* label, float* top_val, int32_t* top_id, float* top_val_user,

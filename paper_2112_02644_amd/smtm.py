@@ -97,6 +97,7 @@ def load_library():
         "smtm_begin_batch": [vp, i32, vp],
         "smtm_encode": [vp, i32, vp, i32, i32, i32, vp, vp, vp],
         "smtm_lookup": [vp, i32, vp, vp, vp, vp],
+        "smtm_separability": [vp, i32, vp, vp, vp],
         "smtm_exit_compact": [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp],
         "smtm_lookup_exit": [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp],
         "smtm_stage": [vp, i32, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp],
@@ -228,6 +229,9 @@ class Smtm:
 
     def lookup(self, exit: int, top_val=None, top_id=None, sims_out=None, stream=None):
         self._ck(self.lib.smtm_lookup(self._h, exit, _ptr(top_val), _ptr(top_id), _ptr(sims_out), self._st(stream)))
+
+    def separability(self, exit: int, sims, sep_out, stream=None):
+        self._ck(self.lib.smtm_separability(self._h, exit, _ptr(sims), _ptr(sep_out), self._st(stream)))
 
     def exit_compact(self, exit: int, exit_ids=None, exit_labels=None, exit_tier=None, n_exit_dev=None,
                      live_ids=None, n_live_dev=None, fmap_in=None, row_ids=None, fmap_out=None,

@@ -613,3 +613,67 @@ def test_warmup_from_a_labelled_stream_then_inference():
     label = np.where(mem.exit_layer > 0, mem.label, truth).astype(np.int32)
     P.check_cache_update(ctx, mem, label, mem.exit_layer.astype(np.int32))
     ctx.close()
+
+
+# ------------------------------------------------------------------ diagnostics
+
+@pytest.mark.parametrize("wname", ["tiny", "resnet18"])
+def test_separability_eq2(wname):
+    w = configs.BY_NAME[wname]
+    cents = streams.centroids(w); ls = streams.labels(w)
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    rtol = P.sim_rtol(w)
+    ctx = P.make_ctx(w, cents, ls.initial_hot, tau=1e6)              # keep (nearly) every frame live
+    ctx.begin_batch(w.batch)
+    hot = np.asarray(ls.initial_hot, np.int32)
+    for l in range(1, w.n_exits + 1):
+        sims = torch.zeros(w.batch, w.n_classes, device=DEV)
+        sep = torch.full((w.batch, 2), float("nan"), device=DEV)
+        live = torch.zeros(w.batch, dtype=torch.int32, device=DEV)
+        n_before, _ = ctx.read_counts()
+        ctx.encode(l, fm[l - 1], row_ids=ctx.live_ids())
+        ctx.lookup(l, sims_out=sims)
+        ctx.separability(l, sims, sep)
+        ctx.exit_compact(l, live_ids=live)
+        torch.cuda.synchronize()
+        s = sims[:n_before].cpu().numpy().astype(np.float64)
+        g = sep[:n_before].cpu().numpy().astype(np.float64)
+        assert torch.isnan(sep[n_before:]).all()
+        checked = 0
+        for i in range(n_before):
+            for t, ids in enumerate((hot, None)):
+                want = O.separability(s[i], ids)                      # the oracle on the library's own similarities
+                if np.isfinite(want):
+                    assert abs(g[i, t] - want) <= 1e-5 * max(1.0, abs(want)), (i, t, g[i, t], want)
+                    checked += 1
+                else:
+                    assert g[i, t] == want
+        assert checked > n_before
+    with pytest.raises(SmtmError) as e:
+        ctx.separability(1, sims, sep)
+    assert e.value.code == 3
+    ctx.close()
+
+
+def test_tau_sweep_diagnostic():
+    from paper_2112_02644_amd import diagnostics
+    w = configs.RESNET18
+    taus = [0.0, 0.5, 2.0, 8.0, 64.0]
+    rows = diagnostics.tau_sweep(w, taus)
+    for r in rows:
+        _say("  ", r)
+        assert abs(sum(r["exit_ratio"]) + r["ran_to_end"] - 1.0) < 1e-9
+        assert 1.0 / (w.n_exits + 1) - 1e-9 <= r["cost_executed"] <= 1.0
+    first = [r["exit_ratio"][0] for r in rows]
+    assert all(a >= b for a, b in zip(first, first[1:]))             # fewer frames leave at the first exit as tau grows
+    assert rows[0]["cost_executed"] <= rows[-1]["cost_executed"]
+    # the per-frame results agree with the oracle's free-running pass at one threshold
+    cents = streams.centroids(w); ls = streams.labels(w, w.batch)
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    mem = P.make_oracle(w, cents, ls.initial_hot, tau=2.0)
+    mem.begin_batch(w.batch)
+    for l in range(1, w.n_exits + 1):
+        mem.stage(l, fm[l - 1].cpu().numpy(), row_ids=mem.live.copy())
+    want = diagnostics.summarise(mem.exit_layer, mem.label, ls.label[: w.batch], w.n_exits)
+    got = rows[2]
+    assert np.allclose(got["exit_ratio"], want["exit_ratio"], atol=2.0 / w.batch)

@@ -671,3 +671,13 @@ def test_warmup_equals_eq7_started_from_count_zero():
     O.centres_update(SC2, m2, [SV], label, np.ones(N, np.int32))
     seen = m > 0
     assert np.allclose(SC2[0][seen], SC[seen], rtol=1e-13) and np.array_equal(m2[0], m)
+
+
+def test_separability_eq2_hand_values_and_sign_cases():
+    assert O.separability(np.array([0.9, 0.3, 0.1])) == pytest.approx(2.0)            # (0.9 - 0.3) / 0.3
+    assert O.separability(np.array([0.9, 0.3, 0.6]), np.array([0, 1], np.int32)) == pytest.approx(2.0)
+    assert O.separability(np.array([0.9, 0.3, 0.6])) == pytest.approx(0.5)            # runner-up is 0.6
+    assert O.separability(np.array([0.5, -0.2])) == np.inf
+    assert O.separability(np.array([-0.5, -0.2])) == -np.inf
+    assert O.separability(np.array([0.5]), np.array([0], np.int32)) == -np.inf
+    assert O.separability(np.array([0.4, 0.4])) == 0.0
