@@ -142,6 +142,11 @@ int32_t smtm_begin_batch(smtm_ctx* ctx, int32_t batch, void* stream);
 int32_t smtm_encode(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype,
                     int32_t H, int32_t W, const int32_t* row_ids, float* sv_out, void* stream);
 
+/* Encode for channels-last feature maps: fmap is [rows, H, W, C_l] (NHWC), otherwise as
+ * smtm_encode.  The semantic vectors are the same as for the NCHW tensor with the same values. */
+int32_t smtm_encode_nhwc(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype,
+                         int32_t H, int32_t W, const int32_t* row_ids, float* sv_out, void* stream);
+
 /* 2. Lookup (Sec. 5 Steps 2-3, Sec. 6): for every live frame s_j = cos(SV, SC_j) for all n
  * classes (Eq. 1; 0 when either vector has zero or non-finite length), SA_j += 2^(exit-1) s_j
  * (Eq. 3), then highest / second-highest SA over the fast memory (tier 1) and over the global

@@ -353,14 +353,18 @@ static int32_t check_encode_args(smtm_ctx* ctx, int32_t exit, const void* fmap, 
     return SMTM_OK;
 }
 
-int32_t smtm_encode(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
-                    const int32_t* row_ids, float* sv_out, void* stream) {
+static int32_t encode_any(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
+                          const int32_t* row_ids, float* sv_out, void* stream, bool channels_last) {
     int32_t rc = check_encode_args(ctx, exit, fmap, dtype, H, W);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int l = exit - 1;
-    launch_encode(fmap, dtype, ctx->cfg.dims[l], H * W, row_ids, ctx->live[ctx->cur], ctx->counts, ctx->batch,
-                  ctx->sv[l], sv_out, st);
+    if (channels_last)
+        launch_encode_nhwc(fmap, dtype, ctx->cfg.dims[l], H * W, row_ids, ctx->live[ctx->cur], ctx->counts,
+                           ctx->batch, ctx->sv[l], sv_out, st);
+    else
+        launch_encode(fmap, dtype, ctx->cfg.dims[l], H * W, row_ids, ctx->live[ctx->cur], ctx->counts, ctx->batch,
+                      ctx->sv[l], sv_out, st);
     rc = check_launch(ctx, "smtm_encode");
     if (rc) return rc;
     ctx->stage_done[l] = 1;
@@ -503,6 +507,16 @@ int32_t smtm_stage(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype,
     if (rc) return rc;
     return smtm_lookup_exit(ctx, exit, nullptr, nullptr, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids,
                             n_live_dev, fmap_out ? fmap : nullptr, row_ids, fmap_out, row_bytes, stream);
+}
+
+int32_t smtm_encode(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
+                    const int32_t* row_ids, float* sv_out, void* stream) {
+    return encode_any(ctx, exit, fmap, dtype, H, W, row_ids, sv_out, stream, false);
+}
+
+int32_t smtm_encode_nhwc(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
+                         const int32_t* row_ids, float* sv_out, void* stream) {
+    return encode_any(ctx, exit, fmap, dtype, H, W, row_ids, sv_out, stream, true);
 }
 
 const int32_t* smtm_live_ids(const smtm_ctx* ctx) { return ctx ? ctx->live[ctx->cur] : nullptr; }

@@ -259,6 +259,114 @@ __global__ __launch_bounds__(256) void k_encode_lds(
     }
 }
 
+// Channels-last (NHWC) feature maps: a frame is H*W position rows of C channels.  A "slab" is up to 64
+// consecutive 16-byte chunks of a position row (512 fp16 or 256 fp32 channels); a lane owns one
+// chunk of the slab (the same channels for every position it visits) and 64 / slab-width positions
+// are read per wavefront load, so loads stay contiguous.  A block handles one (frame, slab); its
+// wavefronts split the positions, partial sums meet in LDS and are added in a fixed order.
+template <typename T, int UNR>
+__global__ __launch_bounds__(1024) void k_encode_nhwc(
+    const T* __restrict__ F, const int32_t* __restrict__ row_ids,
+    const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows,
+    float* __restrict__ sv, float* __restrict__ sv_out, int C, int HW) {
+    constexpr int E = 16 / (int)sizeof(T);               // channels per 16-byte chunk
+    extern __shared__ float part[];                      // [waves][64 lanes][E]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int cpr = C / E;                               // chunks per position row (C is a multiple of E here)
+    const int n_slabs = (cpr + 63) >> 6;
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    const int64_t total = (int64_t)n_live * n_slabs;
+    for (int64_t t = blockIdx.x; t < total; t += gridDim.x) {        // uniform over the block
+        const int slot = (int)(t / n_slabs);
+        const int slab = (int)(t - (int64_t)slot * n_slabs);
+        const int sw = cpr - slab * 64 < 64 ? cpr - slab * 64 : 64;  // chunks in this slab
+        const int ppl = 64 / sw;                                     // positions per wavefront load
+        const int pos_in_load = lane / sw, k = lane - pos_in_load * sw;
+        const bool lane_on = pos_in_load < ppl;
+        const int64_t row = row_ids ? row_ids[slot] : slot;
+        const u32x4* base = reinterpret_cast<const u32x4*>(F + row * (int64_t)HW * C) + slab * 64 + k;
+        // positions of this wavefront: a contiguous share of the H*W positions
+        const int p_lo = (int)((int64_t)HW * wave / nw), p_hi = (int)((int64_t)HW * (wave + 1) / nw);
+        float acc[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] = 0.f;
+        if (lane_on) {
+            for (int p0 = p_lo + pos_in_load; p0 < p_hi; p0 += ppl * UNR) {
+                u32x4 v[UNR];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    const int p = p0 + u * ppl;
+                    if (p < p_hi) v[u] = __builtin_nontemporal_load(base + (int64_t)p * cpr);
+                    else v[u] = u32x4{0u, 0u, 0u, 0u};
+                }
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    if (sizeof(T) == 2) {
+                        const uint32_t w4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const half2_t h = __builtin_bit_cast(half2_t, w4[q]);
+                            acc[(2 * q) % E] += (float)h.x;
+                            acc[(2 * q + 1) % E] += (float)h.y;
+                        }
+                    } else {
+                        const f32x4 f = __builtin_bit_cast(f32x4, v[u]);
+                        acc[0] += f.x; acc[1 % E] += f.y; acc[2 % E] += f.z; acc[3 % E] += f.w;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < E; ++e) part[(wave * 64 + lane) * E + e] = lane_on ? acc[e] : 0.f;
+        __syncthreads();
+        // channel c of the slab = chunk k, element e: add the partial sums of every wavefront and
+        // every position lane that owned chunk k, in a fixed order
+        const int n_out = sw * E;
+        for (int o = threadIdx.x; o < n_out; o += blockDim.x) {
+            const int kk = o / E, e = o - kk * E;
+            float sum = 0.f;
+            for (int w = 0; w < nw; ++w)
+                for (int j = 0; j < ppl; ++j) sum += part[(w * 64 + j * sw + kk) * E + e];
+            const float m = sum / (float)HW;
+            const int c = slab * 64 * E + o;
+            sv[(int64_t)frame_ids[slot] * C + c] = m;
+            if (sv_out) sv_out[(int64_t)slot * C + c] = m;
+        }
+        __syncthreads();
+    }
+}
+
+// Fallback for channel counts that are not a multiple of a 16-byte chunk: lane = channel,
+// positions walked one by one (coalesced over channels).
+template <typename T>
+__global__ __launch_bounds__(256) void k_encode_nhwc_scalar(
+    const T* __restrict__ F, const int32_t* __restrict__ row_ids,
+    const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows,
+    float* __restrict__ sv, float* __restrict__ sv_out, int C, int HW) {
+    int n_live = counts->n_live;
+    if (n_live > max_rows) n_live = max_rows;
+    const int cb = (C + 255) / 256;                      // channel blocks per frame
+    const int64_t total = (int64_t)n_live * cb;
+    for (int64_t t = blockIdx.x; t < total; t += gridDim.x) {
+        const int slot = (int)(t / cb);
+        const int c = (int)(t - (int64_t)slot * cb) * 256 + threadIdx.x;
+        if (c >= C) continue;
+        const int64_t row = row_ids ? row_ids[slot] : slot;
+        const T* p = F + row * (int64_t)HW * C + c;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        int i = 0;
+        for (; i + 4 <= HW; i += 4) {
+            a0 += (float)p[(int64_t)i * C]; a1 += (float)p[(int64_t)(i + 1) * C];
+            a2 += (float)p[(int64_t)(i + 2) * C]; a3 += (float)p[(int64_t)(i + 3) * C];
+        }
+        for (; i < HW; ++i) a0 += (float)p[(int64_t)i * C];
+        const float m = ((a0 + a1) + (a2 + a3)) / (float)HW;
+        sv[(int64_t)frame_ids[slot] * C + c] = m;
+        if (sv_out) sv_out[(int64_t)slot * C + c] = m;
+    }
+}
+
 static int encode_grid(int64_t tasks_upper, int waves_per_block) {
     // enough resident wavefronts to cover HBM latency on 256 CUs, and no more blocks than tasks
     int64_t blocks = (tasks_upper + waves_per_block - 1) / waves_per_block;
@@ -340,6 +448,38 @@ const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int3
     }
     launch_direct<_Float16, 2>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
     return "d2";
+}
+
+const char* launch_encode_nhwc(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
+                               const int32_t* frame_ids, const Counts* counts, int max_rows,
+                               float* sv, float* sv_out, hipStream_t st) {
+    const int E = dtype == SMTM_F16 ? 8 : 4;
+    if (C % E == 0) {
+        const int cpr = C / E;
+        const int n_slabs = (cpr + 63) / 64;
+        const int sw = cpr < 64 ? cpr : 64, ppl = 64 / sw;
+        // wavefronts per block: enough that each still issues several loads, at most 16
+        int nw = HW / (ppl * 8);
+        if (nw < 1) nw = 1;
+        if (nw > 16) nw = 16;
+        const int grid = encode_grid((int64_t)max_rows * n_slabs, 1);
+        const size_t lds = (size_t)nw * 64 * E * sizeof(float);
+        if (dtype == SMTM_F16)
+            hipLaunchKernelGGL((k_encode_nhwc<_Float16, 8>), dim3(grid), dim3(nw * 64), lds, st,
+                               static_cast<const _Float16*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW);
+        else
+            hipLaunchKernelGGL((k_encode_nhwc<float, 8>), dim3(grid), dim3(nw * 64), lds, st,
+                               static_cast<const float*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW);
+        return "nhwc16";
+    }
+    const int grid = encode_grid((int64_t)max_rows * ((C + 255) / 256), 1);
+    if (dtype == SMTM_F16)
+        hipLaunchKernelGGL((k_encode_nhwc_scalar<_Float16>), dim3(grid), dim3(256), 0, st,
+                           static_cast<const _Float16*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW);
+    else
+        hipLaunchKernelGGL((k_encode_nhwc_scalar<float>), dim3(grid), dim3(256), 0, st,
+                           static_cast<const float*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW);
+    return "nhwc1";
 }
 
 }  // namespace smtm

@@ -43,6 +43,11 @@ const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int3
                           const int32_t* frame_ids, const Counts* counts, int max_rows,
                           float* sv_by_frame, float* sv_out_by_slot, hipStream_t st);
 
+// Channels-last variant: fmap is [rows, H, W, C].
+const char* launch_encode_nhwc(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
+                               const int32_t* frame_ids, const Counts* counts, int max_rows,
+                               float* sv_by_frame, float* sv_out_by_slot, hipStream_t st);
+
 // ---- lookup.hip -------------------------------------------------------------------------
 void launch_centre_prepare(const float* centres, int n, int C, float* cinv, _Float16* chat, int Cp,
                            int row_lo, int row_hi, hipStream_t st);

@@ -96,6 +96,7 @@ def load_library():
         "smtm_set_tau": [vp, f32],
         "smtm_begin_batch": [vp, i32, vp],
         "smtm_encode": [vp, i32, vp, i32, i32, i32, vp, vp, vp],
+        "smtm_encode_nhwc": [vp, i32, vp, i32, i32, i32, vp, vp, vp],
         "smtm_lookup": [vp, i32, vp, vp, vp, vp],
         "smtm_separability": [vp, i32, vp, vp, vp],
         "smtm_exit_compact": [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp],
@@ -226,6 +227,14 @@ class Smtm:
             H, W = fmap.shape[2], fmap.shape[3]
         self._ck(self.lib.smtm_encode(self._h, exit, _ptr(fmap), dtype, H, W, _ptr(row_ids), _ptr(sv_out),
                                       self._st(stream)))
+
+    def encode_nhwc(self, exit: int, fmap, row_ids=None, sv_out=None, stream=None, dtype=None, H=None, W=None):
+        """fmap is [rows, H, W, C] (channels last)."""
+        if dtype is None:
+            dtype = _dtype_code(fmap)
+            H, W = fmap.shape[1], fmap.shape[2]
+        self._ck(self.lib.smtm_encode_nhwc(self._h, exit, _ptr(fmap), dtype, H, W, _ptr(row_ids), _ptr(sv_out),
+                                           self._st(stream)))
 
     def lookup(self, exit: int, top_val=None, top_id=None, sims_out=None, stream=None):
         self._ck(self.lib.smtm_lookup(self._h, exit, _ptr(top_val), _ptr(top_id), _ptr(sims_out), self._st(stream)))

@@ -677,3 +677,77 @@ def test_tau_sweep_diagnostic():
     want = diagnostics.summarise(mem.exit_layer, mem.label, ls.label[: w.batch], w.n_exits)
     got = rows[2]
     assert np.allclose(got["exit_ratio"], want["exit_ratio"], atol=2.0 / w.batch)
+
+
+# ------------------------------------------------------------------ channels-last encode
+
+NHWC_SHAPES = [
+    (torch.float16, 5, 256, 14, 14),    # 32 chunks per position, 2 positions per wavefront load
+    (torch.float16, 3, 2048, 7, 7),     # 4 slabs of 64 chunks
+    (torch.float16, 4, 24, 28, 28),     # 3 chunks per position: 21 positions per load, one lane idle
+    (torch.float16, 3, 320, 7, 7),      # 40 chunks: one position per load, 24 lanes idle
+    (torch.float16, 2, 8, 56, 56),      # a single chunk per position, 16 wavefronts split the positions
+    (torch.float16, 3, 1032, 3, 3),     # two slabs, the second one short (65 chunks)
+    (torch.float16, 3, 13, 5, 5),       # channel count not a multiple of 8 -> lane = channel
+    (torch.float32, 4, 64, 14, 14),     # fp32: 4 channels per chunk
+    (torch.float32, 2, 6, 7, 7),        # fp32, not a multiple of 4
+    (torch.float16, 70, 64, 1, 1),      # H*W = 1, more frames than wavefronts per block
+]
+
+
+@pytest.mark.parametrize("dtype,rows,C,H,W", NHWC_SHAPES)
+@pytest.mark.parametrize("use_ids", [False, True])
+def test_encode_nhwc_shapes(dtype, rows, C, H, W, use_ids):
+    _say("encode nhwc", dtype, rows, C, H, W, use_ids)
+    g = torch.Generator().manual_seed(rows * 77 + C)
+    F = (torch.randn(rows, C, H, W, generator=g) * 2 + 0.25).to(dtype)      # NCHW values for the oracle
+    F[0, 0] = 3.0
+    Fl = F.permute(0, 2, 3, 1).contiguous().to(DEV)                          # the same values, channels last
+    batch = rows if not use_ids else max(2, rows - 1)
+    ctx = Smtm(SmtmConfig(n_classes=4, dims=[C], max_batch=rows, hot_init=2))
+    ctx.begin_batch(batch)
+    sv = torch.full((rows, C), float("nan"), device=DEV)
+    ids = None
+    perm = None
+    if use_ids:
+        perm = np.random.default_rng(C).permutation(rows)[:batch].astype(np.int32)
+        ids = torch.from_numpy(perm).to(DEV)
+    ctx.encode_nhwc(1, Fl, row_ids=ids, sv_out=sv)
+    torch.cuda.synchronize()
+    ref = O.encode(F.numpy(), row_ids=perm, n_live=batch)
+    got = sv[:batch].cpu().numpy().astype(np.float64)
+    rows_read = np.arange(batch) if perm is None else perm
+    scale = np.maximum(np.abs(ref), F.float().abs().mean(dim=(2, 3)).numpy()[rows_read])
+    assert (np.abs(got - ref) / scale).max() <= P.SV_RTOL
+    assert torch.isnan(sv[batch:]).all()
+    ctx.close()
+
+
+def test_resnet50_channels_last_batch_matches_oracle_decisions():
+    # the whole path on channels-last tensors: encode_nhwc + lookup_exit with the gather
+    w = dataclasses.replace(configs.RESNET50, batch=256)
+    cents = streams.centroids(w); ls = streams.labels(w)
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    ctx = P.make_ctx(w, cents, ls.initial_hot); mem = P.make_oracle(w, cents, ls.initial_hot)
+    ctx.begin_batch(w.batch); mem.begin_batch(w.batch)
+    flips = 0
+    for l in range(1, w.n_exits + 1):
+        Fl = fm[l - 1].permute(0, 2, 3, 1).contiguous()
+        live_before = mem.live.copy()
+        out_live = torch.zeros(w.batch, dtype=torch.int32, device=DEV)
+        gathered = torch.zeros_like(Fl)
+        ctx.encode_nhwc(l, Fl, row_ids=ctx.live_ids())
+        ctx.lookup_exit(l, live_ids=out_live, fmap_in=Fl, row_ids=ctx.live_ids(), fmap_out=gathered,
+                        row_bytes=Fl[0].numel() * 2)
+        n_live, _ = ctx.read_counts()
+        ref = mem.stage(l, fm[l - 1].cpu().numpy(), row_ids=live_before, live=live_before)
+        g_live = out_live[:n_live].cpu().numpy()
+        for f in np.setxor1d(g_live, ref["live_ids"]):
+            i = int(np.flatnonzero(live_before == f)[0])
+            rv = ref["top_val"][i]
+            assert P.in_band(rv[0, 0], rv[0, 1], w.tau, l, 2e-3) or P.in_band(rv[1, 0], rv[1, 1], w.tau, l, 2e-3)
+            flips += 1
+        assert torch.equal(gathered[:n_live], Fl[torch.from_numpy(g_live.astype(np.int64)).to(DEV)])
+        mem.live = g_live.astype(np.int32)
+    assert flips <= 5
+    ctx.close()
