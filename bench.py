@@ -2,9 +2,9 @@
 """Benchmark of the whole hot path on one MI355X.
 
 A step is one batch of the ResNet-50-shaped workload through every part of the path:
-begin_batch, then at each of the four exit points encode -> lookup -> exit/compact (with the
-survivors' feature maps gathered for the next block), then the per-frame results and the memory
-update.  Inputs (all four feature-map tensors, 3.08 GB) are resident in HBM before the clock
+begin_batch, then at each of the four exit points encode -> lookup -> exit/compact (lists of the
+released frames with labels and tiers, the survivors' feature maps gathered for the next block),
+then the memory update.  Inputs (all four feature-map tensors, 3.08 GB) are resident in HBM before the clock
 starts; nothing is read back inside the timed region.
 
 Prints one JSON line.  `value` is frames/s over the timed steps.  `roofline` is for the dominant
@@ -79,7 +79,10 @@ def main() -> int:
     ctx.hot_set(ls.initial_hot)
 
     i32 = dict(dtype=torch.int32, device=dev)
-    res_layer = torch.zeros(B, **i32); res_label = torch.zeros(B, **i32); res_tier = torch.zeros(B, **i32)
+    # what a caller gets back per exit point: ids, labels and tiers of the frames released there
+    exit_ids = [torch.zeros(B, **i32) for _ in range(L)]
+    exit_labels = [torch.zeros(B, **i32) for _ in range(L)]
+    exit_tier = [torch.zeros(B, **i32) for _ in range(L)]
     total = args.steps + args.warmup
     live_log = torch.zeros((total, L), **i32)              # survivors after each exit point, per step
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
@@ -101,10 +104,10 @@ def main() -> int:
                 b.record()
             else:
                 ctx.encode(l, F, row_ids=ids)
-            ctx.lookup_exit(l, n_live_dev=live_ptr0 + 4 * (s * L + l - 1), fmap_in=F, row_ids=ids,
+            ctx.lookup_exit(l, exit_ids=exit_ids[l - 1], exit_labels=exit_labels[l - 1], exit_tier=exit_tier[l - 1],
+                            n_live_dev=live_ptr0 + 4 * (s * L + l - 1), fmap_in=F, row_ids=ids,
                             fmap_out=gathers[l - 1], row_bytes=F[0].numel() * esz)
-        ctx.batch_results(res_layer, res_label, res_tier)
-        ctx.cache_update(res_label, res_layer, B)
+        ctx.cache_update(None, None, B)                     # memory update with the batch's own exits
 
     for s in range(args.warmup):
         step(s)

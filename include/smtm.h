@@ -228,6 +228,8 @@ int32_t smtm_read_stats(smtm_ctx* ctx, int32_t* stats_host, void* stream);
  *   label[b]      device int32 [batch]: recognised class or -1 (nothing recognised)
  *   stop_layer[b] device int32 [batch]: exit point at which inference stopped, 0 = do not
  *                 update centres with this frame
+ *   Both NULL: the batch's own results are used (what smtm_batch_results would return: label
+ *   and exit point of the frames released so far, -1 / 0 for the others).
  * (i)  FT_j += 1 for the frame's class, TS_i = consecutive frames without class i (Sec. 6.1);
  * (ii) centres of class label[b] at exit points 1..stop_layer[b] move to the running mean
  *      (SC*m + SV)/(m+1) with the semantic vectors saved by smtm_encode (Eq. 7);

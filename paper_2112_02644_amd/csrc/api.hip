@@ -599,17 +599,19 @@ int32_t smtm_warmup_batch(smtm_ctx* ctx, const int32_t* label, int32_t batch, vo
 
 int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* stop_layer, int32_t batch, void* stream) {
     if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
-    if (!label || !stop_layer) return fail(ctx, SMTM_ERR_INVALID_ARG, "label / stop_layer is NULL");
+    if ((label == nullptr) != (stop_layer == nullptr))
+        return fail(ctx, SMTM_ERR_INVALID_ARG, "label and stop_layer must be given together (or both NULL)");
     if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");
+    if (!label) { label = ctx->res_label; stop_layer = ctx->res_layer; }     // the batch's own exits
     if (batch != ctx->batch) return fail(ctx, SMTM_ERR_SHAPE, "batch %d differs from the batch begun (%d)", batch, ctx->batch);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const smtm_config& c = ctx->cfg;
     const int n = c.n_classes;
     launch_tables_update(label, batch, n, (uint32_t)c.window, ctx->FT, ctx->TS, ctx->cls_cnt, ctx->cls_last,
                          ctx->score, ctx->score_total, ctx->below, c.forgetting, st);
-    launch_centres_update(centre_tables(ctx), c.n_exits, n, label, stop_layer, batch, ctx->cls_cnt, st);
-    launch_policy(ctx->score, ctx->score_total, n, (uint32_t)c.cl_num, (uint32_t)c.cl_den, c.hot_min, c.hot_max,
-                  ctx->order, ctx->below, ctx->hot_ids, ctx->in_hot, ctx->counts, st);
+    launch_centres_and_policy(centre_tables(ctx), c.n_exits, n, label, stop_layer, batch, ctx->cls_cnt, ctx->score,
+                              ctx->score_total, (uint32_t)c.cl_num, (uint32_t)c.cl_den, c.hot_min, c.hot_max,
+                              ctx->order, ctx->below, ctx->hot_ids, ctx->in_hot, ctx->counts, st);
     return check_launch(ctx, "smtm_cache_update");
 }
 

@@ -96,8 +96,10 @@ void launch_tables_update(const int32_t* label, int batch, int n, uint32_t W, ui
 void launch_class_count(const int32_t* label, int batch, int n, uint32_t* cls_cnt, hipStream_t st);
 void launch_centres_update(const CentreTables& tabs, int n_exits, int n, const int32_t* label,
                            const int32_t* stop_layer, int batch, const uint32_t* cls_cnt, hipStream_t st);
-void launch_policy(const uint64_t* score, const uint64_t* total, int n, uint32_t cl_num, uint32_t cl_den,
-                   int hot_min, int hot_max, int32_t* order, int32_t* below, int32_t* hot_ids,
-                   uint8_t* in_hot, Counts* counts, hipStream_t st);
+void launch_centres_and_policy(const CentreTables& tabs, int n_exits, int n, const int32_t* label,
+                               const int32_t* stop_layer, int batch, const uint32_t* cls_cnt,
+                               const uint64_t* score, const uint64_t* total, uint32_t cl_num, uint32_t cl_den,
+                               int hot_min, int hot_max, int32_t* order, int32_t* below, int32_t* hot_ids,
+                               uint8_t* in_hot, Counts* counts, hipStream_t st);
 
 }  // namespace smtm

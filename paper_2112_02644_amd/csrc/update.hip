@@ -154,13 +154,12 @@ void launch_class_count(const int32_t* label, int batch, int n, uint32_t* cls_cn
 // fp16 copy of the row.
 constexpr int kListCap = 4096;
 
-__global__ __launch_bounds__(256) void k_centres_update(CentreTables tabs, int n, const int32_t* __restrict__ label,
-                                                        const int32_t* __restrict__ stop_layer, int batch,
-                                                        const uint32_t* __restrict__ cls_cnt) {
+__device__ __forceinline__ void centres_block(const CentreTables& tabs, const int32_t* __restrict__ label,
+                                              const int32_t* __restrict__ stop_layer, int batch,
+                                              const uint32_t* __restrict__ cls_cnt, int j, int l0) {
     __shared__ int list[kListCap];
     __shared__ int w_cnt[4];
     __shared__ float red[4];
-    const int j = blockIdx.x, l0 = blockIdx.y;
     if (cls_cnt[j] == 0) return;                         // uniform over the block
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int C = tabs.C[l0], Cp = tabs.Cp[l0];
@@ -230,28 +229,36 @@ __global__ __launch_bounds__(256) void k_centres_update(CentreTables tabs, int n
     }
 }
 
+__global__ __launch_bounds__(256) void k_centres_update(CentreTables tabs, int n, const int32_t* __restrict__ label,
+                                                        const int32_t* __restrict__ stop_layer, int batch,
+                                                        const uint32_t* __restrict__ cls_cnt) {
+    centres_block(tabs, label, stop_layer, batch, cls_cnt, blockIdx.x, blockIdx.y);
+}
+
 void launch_centres_update(const CentreTables& tabs, int n_exits, int n, const int32_t* label,
                            const int32_t* stop_layer, int batch, const uint32_t* cls_cnt, hipStream_t st) {
     hipLaunchKernelGGL(k_centres_update, dim3(n, n_exits), dim3(256), 0, st, tabs, n, label, stop_layer,
                        batch, cls_cnt);
 }
 
-// Replacement policy and adaptive size (Eq. 5, Eq. 6), two launches.
+// Replacement policy and adaptive size (Eq. 5, Eq. 6).
 //   rank_i  = number of classes ahead of i in (score desc, id asc) order
 //   prefix_i = sum of the scores of the classes up to and including i in that order
 //   k       = 1 + number of classes whose prefix is still below CL * total
 //             (the prefix share is non-decreasing along the order), clamped to [hot_min, hot_max]
-// k_policy_rank: 16 lanes per class split the scan over all classes and combine with shuffles.
+// rank_block: 16 lanes per class split the scan over all classes and combine with shuffles.
+// The ranks only need the scores, the centres only the class counts: both come from
+// k_tables_update, so the two share one launch (k_centres_and_rank) and run side by side.
 constexpr int kRankTile = 2048;            // scores staged per pass (16 KB of LDS)
 
-__global__ __launch_bounds__(256) void k_policy_rank(const uint64_t* __restrict__ score,
-                                                     const uint64_t* __restrict__ total, int n,
-                                                     uint32_t cl_num, uint32_t cl_den,
-                                                     int32_t* __restrict__ order,
-                                                     int32_t* __restrict__ below) {
+__device__ __forceinline__ void rank_block(const uint64_t* __restrict__ score,
+                                           const uint64_t* __restrict__ total, int n,
+                                           uint32_t cl_num, uint32_t cl_den,
+                                           int32_t* __restrict__ order,
+                                           int32_t* __restrict__ below, int block) {
     __shared__ uint64_t tile[kRankTile];
     const int tid = threadIdx.x, sub = tid & 15;
-    const int i = blockIdx.x * 16 + (tid >> 4);
+    const int i = block * 16 + (tid >> 4);
     const bool valid = i < n;
     const uint64_t si = valid ? score[i] : 0;            // issued before the total is needed
     const u128 tot = ((u128)total[1] << 64) | total[0];
@@ -283,6 +290,25 @@ __global__ __launch_bounds__(256) void k_policy_rank(const uint64_t* __restrict_
     }
 }
 
+__global__ __launch_bounds__(256) void k_centres_and_rank(CentreTables tabs, int n_exits, int n,
+                                                          const int32_t* __restrict__ label,
+                                                          const int32_t* __restrict__ stop_layer, int batch,
+                                                          const uint32_t* __restrict__ cls_cnt,
+                                                          const uint64_t* __restrict__ score,
+                                                          const uint64_t* __restrict__ total,
+                                                          uint32_t cl_num, uint32_t cl_den,
+                                                          int32_t* __restrict__ order,
+                                                          int32_t* __restrict__ below) {
+    const int n_rank = (n + 15) / 16;                    // the rank blocks come first: all of them have work
+    const int b = blockIdx.x;
+    if (b < n_rank) {
+        rank_block(score, total, n, cl_num, cl_den, order, below, b);
+    } else {
+        const int r = b - n_rank;
+        centres_block(tabs, label, stop_layer, batch, cls_cnt, r % n, r / n);
+    }
+}
+
 __global__ __launch_bounds__(1024) void k_policy_finish(const uint64_t* __restrict__ total, int n,
                                                         int hot_min, int hot_max,
                                                         const int32_t* __restrict__ order,
@@ -305,11 +331,14 @@ __global__ __launch_bounds__(1024) void k_policy_finish(const uint64_t* __restri
     if (tid == 0) counts->hot_k = k;
 }
 
-void launch_policy(const uint64_t* score, const uint64_t* total, int n, uint32_t cl_num, uint32_t cl_den,
-                   int hot_min, int hot_max, int32_t* order, int32_t* below, int32_t* hot_ids,
-                   uint8_t* in_hot, Counts* counts, hipStream_t st) {
-    hipLaunchKernelGGL(k_policy_rank, dim3((n + 15) / 16), dim3(256), 0, st, score, total, n, cl_num, cl_den,
-                       order, below);
+void launch_centres_and_policy(const CentreTables& tabs, int n_exits, int n, const int32_t* label,
+                               const int32_t* stop_layer, int batch, const uint32_t* cls_cnt,
+                               const uint64_t* score, const uint64_t* total, uint32_t cl_num, uint32_t cl_den,
+                               int hot_min, int hot_max, int32_t* order, int32_t* below, int32_t* hot_ids,
+                               uint8_t* in_hot, Counts* counts, hipStream_t st) {
+    const int blocks = (n + 15) / 16 + n * n_exits;
+    hipLaunchKernelGGL(k_centres_and_rank, dim3(blocks), dim3(256), 0, st, tabs, n_exits, n, label, stop_layer,
+                       batch, cls_cnt, score, total, cl_num, cl_den, order, below);
     hipLaunchKernelGGL(k_policy_finish, dim3(1), dim3(1024), 0, st, total, n, hot_min, hot_max, order, below,
                        hot_ids, in_hot, counts);
 }

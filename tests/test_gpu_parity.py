@@ -808,3 +808,32 @@ def test_adaptive_stream_full_length():
     assert w.hot_min <= min(hot_sizes) and max(hot_sizes) <= w.hot_max and len(set(hot_sizes)) > 3
     assert rep.in_band_flips <= rep.frames // 50
     assert exits_total[0] < 0.2 * w.total_frames            # with the update running, most frames are released early
+
+
+def test_cache_update_with_the_batchs_own_results():
+    # NULL label / stop_layer = the context's per-frame results of the batch
+    w = configs.RESNET18
+    cents = streams.centroids(w); ls = streams.labels(w)
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    outs = []
+    for own in (False, True):
+        ctx = P.make_ctx(dataclasses.replace(w, hot_min=4, hot_max=64), cents, ls.initial_hot)
+        for _ in range(2):
+            ctx.begin_batch(w.batch)
+            for l in range(1, w.n_exits + 1):
+                ctx.stage(l, fm[l - 1], row_ids=ctx.live_ids())
+            if own:
+                ctx.cache_update(None, None, w.batch)
+            else:
+                res = [torch.zeros(w.batch, dtype=torch.int32, device=DEV) for _ in range(3)]
+                ctx.batch_results(*res)
+                ctx.cache_update(res[1], res[0], w.batch)
+        torch.cuda.synchronize()
+        outs.append(([ctx.memory_export(l) for l in range(1, w.n_exits + 1)], ctx.tables_export()))
+        with pytest.raises(SmtmError):
+            ctx.cache_update(torch.zeros(w.batch, dtype=torch.int32, device=DEV), None, w.batch)
+        ctx.close()
+    for (c1, m1), (c2, m2) in zip(outs[0][0], outs[1][0]):
+        assert np.array_equal(c1.view(np.int32), c2.view(np.int32)) and np.array_equal(m1, m2)
+    for a, b in zip(outs[0][1], outs[1][1]):
+        assert np.array_equal(a, b)
