@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
 # profiles/encode_direct_f16_hbm_traffic.txt (same command, same workload).  Reported only while the kernel's
 # source is the one the counters were taken on; otherwise the field is null.
-TRAFFIC = {"workload": "resnet50", "bytes_per_launch": 972828895.0,
-           "encode_sha256": "789fdebb3af62aca5853e9faf68d60074928e439c798f13e9fd36d53def7d8ce"}
+TRAFFIC = {"workload": "resnet50", "bytes_per_launch": 972899941.0,
+           "encode_sha256": "9343382150fbaba695e3f771026f3ca65ee683d563d6803eac2cbbd1f6bad5ae"}
 
 
 def measured_traffic(workload: str):
