@@ -37,8 +37,14 @@ def build(force: bool = True) -> Path:
 def lib():
     global _lib
     if _lib is None:
-        build(force=False)
-        L = C.CDLL(str(_LIB))
+        # SMTM_ORACLE_LIB: a test may point this module at a deliberately broken build of the oracle
+        # to show that the pins notice (tests/test_oracle_mutations.py)
+        override = os.environ.get("SMTM_ORACLE_LIB")
+        if override:
+            L = C.CDLL(override)
+        else:
+            build(force=False)
+            L = C.CDLL(str(_LIB))
         dp, ip, vp = C.POINTER(C.c_double), C.POINTER(C.c_int32), C.c_void_p
         up = C.POINTER(C.c_uint32)
         L.orc_half_to_double.restype = C.c_double
