@@ -837,3 +837,61 @@ def test_cache_update_with_the_batchs_own_results():
         assert np.array_equal(c1.view(np.int32), c2.view(np.int32)) and np.array_equal(m1, m2)
     for a, b in zip(outs[0][1], outs[1][1]):
         assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------ large class counts, large batches, degenerate streams
+
+def test_many_classes_and_long_batch():
+    # n > 4096 (class histogram and scores no longer fit the LDS tiles), batch > 4096 (several
+    # passes of the compaction block, more frames of one class than the centre kernel's list holds)
+    n, B = 5000, 4500
+    w = dataclasses.replace(configs.ADAPTIVE, n_classes=n, batch=B, exits=((24, 2, 2), (40, 1, 1)), hot=40,
+                            hot_min=8, hot_max=4000, window=1000, zipf_s=1.6, total_frames=2 * B, drift_every=0,
+                            sigma=0.2, tau=1.0, init_count=5)
+    cents = streams.centroids(w)
+    ls = streams.labels(w, 2 * B)
+    ctx = P.make_ctx(w, cents, ls.initial_hot)
+    mem = P.make_oracle(w, cents, ls.initial_hot)
+    rep = P.ParityReport()
+    for b in range(2):
+        fm = streams.batch_feature_maps(w, cents, ls, b, DEV)
+        P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), check_sims=(b == 0), report=rep,
+                      fused=("lookup_exit" if b else False))
+        truth = ls.label[b * B:(b + 1) * B]
+        label = np.where(mem.exit_layer > 0, mem.label, truth).astype(np.int32)
+        if b == 1:
+            label[:] = label[0]                            # one class gets every frame: > 4096 frames in its list
+        stop = np.where(mem.exit_layer > 0, mem.exit_layer, 2).astype(np.int32)
+        upd, e = P.check_cache_update(ctx, mem, label, stop)
+        _say(f"  batch {b}: exits {rep.exit_hist} hot size {len(mem.hot_ids)} centre err {e:.2e}")
+    assert rep.in_band_flips <= rep.frames // 50
+    ctx.close()
+
+
+def test_limits_of_the_context():
+    # the largest class count the library accepts, tiny everything else
+    n = 16384
+    ctx = Smtm(SmtmConfig(n_classes=n, dims=[8], max_batch=6, hot_init=2, hot_min=2, hot_max=n))
+    rng = np.random.default_rng(5)
+    cents = rng.standard_normal((n, 8)).astype(np.float32)
+    ctx.memory_load(1, cents)
+    F = torch.from_numpy(cents[[3, 16383, 9000, 3, 77, 12345]].reshape(6, 8, 1, 1)).to(DEV)
+    ctx.set_tau(0.0)
+    ctx.begin_batch(6)
+    top_val = torch.zeros(6, 2, 2, device=DEV); top_id = torch.zeros(6, 2, dtype=torch.int32, device=DEV)
+    labels = torch.zeros(6, dtype=torch.int32, device=DEV); ids = torch.zeros(6, dtype=torch.int32, device=DEV)
+    n_exit = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ctx.encode(1, F)
+    ctx.lookup_exit(1, top_val=top_val, top_id=top_id, exit_ids=ids, exit_labels=labels, n_exit_dev=n_exit)
+    torch.cuda.synchronize()
+    # a frame whose semantic vector IS a centre scores cosine 1 with it: best class over the whole memory
+    want = [3, 16383, 9000, 3, 77, 12345]
+    assert top_id[:, 1].cpu().tolist() == want
+    assert np.allclose(top_val[:, 1, 0].cpu().numpy(), 1.0, atol=2e-6)
+    k = int(n_exit.item())
+    assert k == 6                                          # tau = 0: everything with a positive best score leaves
+    ctx.cache_update(None, None, 6)
+    ft, ts, hot, kk = ctx.tables_export()
+    lab = labels[:k].cpu().numpy()
+    assert ft.sum() == k and np.array_equal(np.bincount(lab, minlength=n), ft) and kk >= 2
+    ctx.close()
