@@ -72,12 +72,15 @@ template <> struct Chunk<float, 4> {
     static __device__ __forceinline__ float sum(V v) { return v; }
 };
 
-template <typename T, int VB, int UNR>
+// GL >= 0 fixes the lanes per channel (2^GL) at compile time, which the 16-byte path uses: the
+// load offsets and the reduction tree become constants.  GL < 0 takes it from the argument.
+template <typename T, int VB, int UNR, int GL>
 __global__ __launch_bounds__(256) void k_encode_direct(
     const T* __restrict__ F, const int32_t* __restrict__ row_ids,
     const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows,
-    float* __restrict__ sv, float* __restrict__ sv_out, int C, int HW, int g_log2) {
+    float* __restrict__ sv, float* __restrict__ sv_out, int C, int HW, int g_log2_arg) {
     typedef typename Chunk<T, VB>::V V;
+    const int g_log2 = GL >= 0 ? GL : g_log2_arg;
     const int lane = threadIdx.x & 63;
     const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const int n_waves = gridDim.x * (blockDim.x >> 6);
@@ -387,9 +390,24 @@ static void launch_direct(const void* fmap, int C, int HW, const int32_t* row_id
     const int cpw = 64 >> g_log2;
     const int64_t tasks = (int64_t)max_rows * ((C + cpw - 1) / cpw);
     const int grid = encode_grid(tasks, 4);
-    hipLaunchKernelGGL((k_encode_direct<T, VB, UNR>), dim3(grid), dim3(256), 0, st,
-                       static_cast<const T*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out,
-                       C, HW, g_log2);
+    const T* F = static_cast<const T*>(fmap);
+#define SMTM_LAUNCH_DIRECT(GL)                                                                              \
+    hipLaunchKernelGGL((k_encode_direct<T, VB, UNR, GL>), dim3(grid), dim3(256), 0, st, F, row_ids, frame_ids, \
+                       counts, max_rows, sv, sv_out, C, HW, g_log2)
+    if (VB == 16) {
+        switch (g_log2) {
+            case 0: SMTM_LAUNCH_DIRECT(0); break;
+            case 1: SMTM_LAUNCH_DIRECT(1); break;
+            case 2: SMTM_LAUNCH_DIRECT(2); break;
+            case 3: SMTM_LAUNCH_DIRECT(3); break;
+            case 4: SMTM_LAUNCH_DIRECT(4); break;
+            case 5: SMTM_LAUNCH_DIRECT(5); break;
+            default: SMTM_LAUNCH_DIRECT(6); break;
+        }
+    } else {
+        SMTM_LAUNCH_DIRECT(-1);
+    }
+#undef SMTM_LAUNCH_DIRECT
 }
 
 template <typename T>
