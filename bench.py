@@ -53,7 +53,7 @@ def main() -> int:
     ap.add_argument("--cpu-sample", type=int, default=1024, help="frames of the batch given to the CPU oracle")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 (frames are independent, so more GPUs "
+        print("bench.py: this library runs on one GPU; --gpus must be 1 (frames are independent, so more GPUs "
               "would each take a share of the batch with the memory tables replicated)", file=sys.stderr)
         return 2
 

@@ -65,7 +65,6 @@ struct smtm_ctx {
     int batch;                                   // 0 = no batch begun
     int stage_done[SMTM_MAX_EXITS];              // 0 none, 1 encoded, 2 looked up, 3 compacted
     int enc_dtype[SMTM_MAX_EXITS];
-    int bound[SMTM_MAX_EXITS + 1];               // host upper bound of live rows entering exit point l (0-based)
     std::vector<void*> allocs;
 };
 
@@ -338,7 +337,6 @@ int32_t smtm_begin_batch(smtm_ctx* ctx, int32_t batch, void* stream) {
     if (rc) return rc;
     ctx->batch = batch;
     for (int l = 0; l < SMTM_MAX_EXITS; ++l) ctx->stage_done[l] = 0;
-    for (int l = 0; l <= SMTM_MAX_EXITS; ++l) ctx->bound[l] = batch;
     return SMTM_OK;
 }
 

@@ -18,7 +18,7 @@ def declared_functions():
     return sorted(set(names))
 
 
-def test_header_declares_the_four_north_star_calls():
+def test_header_declares_the_four_core_calls():
     names = declared_functions()
     for must in ("smtm_encode", "smtm_lookup", "smtm_exit_compact", "smtm_cache_update"):
         assert must in names

@@ -133,7 +133,7 @@ def test_cosine_zero_or_nonfinite_vector_gives_zero():
 
 
 def test_lookup_cached_vector_scores_one_against_itself():
-    # spec invariant: a frame whose semantic vector IS centre j scores cosine 1 with j.
+    # a frame whose semantic vector IS centre j scores cosine 1 with j.
     n, C = 12, 64
     SC = rng.standard_normal((n, C))
     SA = np.zeros((n, n))
