@@ -868,6 +868,30 @@ def test_many_classes_and_long_batch():
     ctx.close()
 
 
+def test_largest_batch():
+    # 65536 frames, the most a context accepts: 64 chunks of the compaction block, live lists and
+    # per-frame results at their longest; small maps keep the oracle quick
+    B = 65536
+    w = dataclasses.replace(configs.TINY, batch=B, n_classes=64, exits=((16, 2, 2), (8, 1, 1)), hot=8, zipf_s=1.2,
+                            sigma=0.25, tau=1.0)
+    cents = streams.centroids(w)
+    ls = streams.labels(w, B)
+    ctx = P.make_ctx(w, cents, ls.initial_hot)
+    mem = P.make_oracle(w, cents, ls.initial_hot)
+    rep = P.ParityReport()
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), check_sims=False, report=rep,
+                  fused="lookup_exit")
+    _say(f"  exits {rep.exit_hist} tiers {rep.tier_hist} flips {rep.in_band_flips}")
+    assert sum(rep.exit_hist) == B and rep.exit_hist[1] > 0 and rep.exit_hist[0] > 0
+    assert rep.in_band_flips <= B // 1000
+    label = np.where(mem.exit_layer > 0, mem.label, np.maximum(ls.label[:B], 0)).astype(np.int32)
+    stop = np.where(mem.exit_layer > 0, mem.exit_layer, 2).astype(np.int32)
+    # a class sums tens of thousands of fp32 vectors here: rounding grows like eps * sqrt(count) ~ 1.5e-5
+    P.check_cache_update(ctx, mem, label, stop, centre_rtol=1e-4)
+    ctx.close()
+
+
 def test_limits_of_the_context():
     # the largest class count the library accepts, tiny everything else
     n = 16384
