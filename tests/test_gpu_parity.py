@@ -388,6 +388,61 @@ def test_two_runs_are_bit_identical():
         assert np.array_equal(a.view(np.int32), b.view(np.int32))
 
 
+def test_two_contexts_on_two_streams_do_not_disturb_each_other():
+    # a serving process keeps one context per model and drives them from different streams: the calls of
+    # two contexts interleaved on two streams give, bit for bit, what each gives alone
+    ws = [configs.RESNET18, dataclasses.replace(configs.TINY, batch=64)]
+    data = []
+    for w in ws:
+        cents = streams.centroids(w); ls = streams.labels(w)
+        data.append((w, cents, ls, streams.batch_feature_maps(w, cents, ls, 0, DEV)))
+
+    def calls(w, ctx, fm, out):
+        """The calls of one batch as a list of thunks, so that two lists can be interleaved."""
+        B = w.batch
+        seq = [lambda: ctx.begin_batch(B)]
+        for l in range(1, w.n_exits + 1):
+            seq.append(lambda l=l: ctx.encode(l, fm[l - 1], row_ids=ctx.live_ids()))
+            seq.append(lambda l=l: ctx.lookup(l))
+            seq.append(lambda l=l: ctx.exit_compact(l))
+        seq.append(lambda: ctx.batch_results(*out))
+        seq.append(lambda: ctx.cache_update(None, None, B))
+        return seq
+
+    def snapshot(w, ctx, out):
+        torch.cuda.synchronize()
+        cen = [ctx.memory_export(l)[0] for l in range(1, w.n_exits + 1)]
+        return [o.cpu().numpy().copy() for o in out] + [c.view(np.int32) for c in cen] + list(ctx.tables_export()[:3])
+
+    alone = []
+    for w, cents, ls, fm in data:
+        ctx = P.make_ctx(w, cents, ls.initial_hot)
+        out = [torch.zeros(w.batch, dtype=torch.int32, device=DEV) for _ in range(3)]
+        for c in calls(w, ctx, fm, out):
+            c()
+        alone.append(snapshot(w, ctx, out))
+        ctx.close()
+
+    side = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ctxs, outs, seqs = [], [], []
+    for (w, cents, ls, fm), st in zip(data, side):
+        ctx = P.make_ctx(w, cents, ls.initial_hot)
+        ctx.stream = st.cuda_stream
+        out = [torch.zeros(w.batch, dtype=torch.int32, device=DEV) for _ in range(3)]
+        ctxs.append(ctx); outs.append(out); seqs.append(calls(w, ctx, fm, out))
+    torch.cuda.synchronize()
+    for i in range(max(len(q) for q in seqs)):
+        for q in seqs:
+            if i < len(q):
+                q[i]()
+    for (w, _, _, _), ctx, out, ref in zip(data, ctxs, outs, alone):
+        got = snapshot(w, ctx, out)
+        assert (got[0] > 0).any()                          # something was released
+        for a, b in zip(got, ref):
+            assert np.array_equal(a, b)
+        ctx.close()
+
+
 # ------------------------------------------------------------------ call-order and argument errors
 
 def test_call_order_and_argument_errors():
