@@ -21,7 +21,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Hot calls only
  *     enqueue; they never synchronise.  All calls on one context must be issued on one stream
  *     (or be otherwise ordered by the caller).  A context is bound to the GPU that was current
- *     when it was created.
+ *     when it was created; calls made while another GPU is current fail with SMTM_ERR_STATE.
  *   - Exit points are numbered 1..L in network order; that number is the l of weight 2^(l-1).
  *     Classes are 0..n-1.  Frames of a batch are 0..batch-1 ("original frame id").
  *     "Slot" i is the i-th live frame, live frames being kept in ascending original id.
@@ -201,6 +201,12 @@ int32_t smtm_stage(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype,
                    int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
                    int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev,
                    void* fmap_out, void* stream);
+/* The same for a channels-last feature map [rows, H, W, C_l] (smtm_encode_nhwc in place of smtm_encode). */
+int32_t smtm_stage_nhwc(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype,
+                        int32_t H, int32_t W, const int32_t* row_ids,
+                        int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
+                        int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev,
+                        void* fmap_out, void* stream);
 
 /* Device pointer to the context's current live list (original frame ids, ascending; the live
  * count is on the device, see smtm_read_counts).  Valid as row_ids for smtm_encode /

@@ -130,8 +130,18 @@ static int32_t validate_config(const smtm_config* c) {
     return SMTM_OK;
 }
 
-static int32_t check_ctx_exit(smtm_ctx* ctx, int32_t exit) {
+// Every call that touches the GPU starts here: the context's buffers live on one GPU, and a launch
+// from a thread whose current device is another one would hand them to the wrong device.
+static int32_t check_ctx(smtm_ctx* ctx) {
     if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device)
+        return fail(ctx, SMTM_ERR_STATE, "the context lives on GPU %d but the current device is %d", ctx->device, dev);
+    return SMTM_OK;
+}
+
+static int32_t check_ctx_exit(smtm_ctx* ctx, int32_t exit) {
+    if (int32_t rc = check_ctx(ctx)) return rc;
     if (exit < 1 || exit > ctx->cfg.n_exits)
         return fail(ctx, SMTM_ERR_INVALID_ARG, "exit point %d outside 1..%d", exit, ctx->cfg.n_exits);
     return SMTM_OK;
@@ -264,7 +274,7 @@ int32_t smtm_memory_load(smtm_ctx* ctx, int32_t exit, const float* centres_host,
 }
 
 int32_t smtm_hot_set(smtm_ctx* ctx, const int32_t* ids, int32_t k, void* stream) {
-    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (int32_t rc = check_ctx(ctx)) return rc;
     if (!ids) return fail(ctx, SMTM_ERR_INVALID_ARG, "class_ids_host is NULL");
     if (k < ctx->cfg.hot_min || k > ctx->cfg.hot_max)
         return fail(ctx, SMTM_ERR_INVALID_ARG, "k = %d outside hot_min..hot_max (%d..%d)", k, ctx->cfg.hot_min, ctx->cfg.hot_max);
@@ -295,7 +305,7 @@ int32_t smtm_memory_export(smtm_ctx* ctx, int32_t exit, float* centres_host, uin
 }
 
 int32_t smtm_tables_export(smtm_ctx* ctx, uint32_t* ft, uint32_t* ts, int32_t* hot_ids, int32_t* k, void* stream) {
-    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (int32_t rc = check_ctx(ctx)) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int n = ctx->cfg.n_classes;
     Counts c;
@@ -309,7 +319,7 @@ int32_t smtm_tables_export(smtm_ctx* ctx, uint32_t* ft, uint32_t* ts, int32_t* h
 }
 
 int32_t smtm_tables_import(smtm_ctx* ctx, const uint32_t* ft, const uint32_t* ts, void* stream) {
-    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (int32_t rc = check_ctx(ctx)) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int n = ctx->cfg.n_classes;
     if (ft) HIP_TRY(ctx, hipMemcpyAsync(ctx->FT, ft, sizeof(uint32_t) * (size_t)n, hipMemcpyHostToDevice, st));
@@ -326,7 +336,7 @@ int32_t smtm_set_tau(smtm_ctx* ctx, float tau) {
 }
 
 int32_t smtm_begin_batch(smtm_ctx* ctx, int32_t batch, void* stream) {
-    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (int32_t rc = check_ctx(ctx)) return rc;
     if (batch < 1 || batch > ctx->cfg.max_batch)
         return fail(ctx, SMTM_ERR_SHAPE, "batch %d outside 1..max_batch (%d)", batch, ctx->cfg.max_batch);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -492,19 +502,34 @@ int32_t smtm_lookup_exit(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* t
     return SMTM_OK;
 }
 
-int32_t smtm_stage(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
-                   const int32_t* row_ids, int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
-                   int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev, void* fmap_out, void* stream) {
+static int32_t stage_any(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
+                         const int32_t* row_ids, int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
+                         int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev, void* fmap_out, void* stream,
+                         bool channels_last) {
     int32_t rc = check_encode_args(ctx, exit, fmap, dtype, H, W);
     if (rc) return rc;
     const int l = exit - 1;
     const int64_t row_bytes = (int64_t)ctx->cfg.dims[l] * H * W * (dtype == SMTM_F16 ? 2 : 4);
     rc = check_compact_args(ctx, live_ids, fmap_out ? fmap : nullptr, row_ids, fmap_out, row_bytes);
     if (rc) return rc;
-    rc = smtm_encode(ctx, exit, fmap, dtype, H, W, row_ids, nullptr, stream);
+    rc = encode_any(ctx, exit, fmap, dtype, H, W, row_ids, nullptr, stream, channels_last);
     if (rc) return rc;
     return smtm_lookup_exit(ctx, exit, nullptr, nullptr, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids,
                             n_live_dev, fmap_out ? fmap : nullptr, row_ids, fmap_out, row_bytes, stream);
+}
+
+int32_t smtm_stage(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
+                   const int32_t* row_ids, int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
+                   int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev, void* fmap_out, void* stream) {
+    return stage_any(ctx, exit, fmap, dtype, H, W, row_ids, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids,
+                     n_live_dev, fmap_out, stream, false);
+}
+
+int32_t smtm_stage_nhwc(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
+                        const int32_t* row_ids, int32_t* exit_ids, int32_t* exit_labels, int32_t* exit_tier,
+                        int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev, void* fmap_out, void* stream) {
+    return stage_any(ctx, exit, fmap, dtype, H, W, row_ids, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids,
+                     n_live_dev, fmap_out, stream, true);
 }
 
 int32_t smtm_encode(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W,
@@ -520,7 +545,7 @@ int32_t smtm_encode_nhwc(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t 
 const int32_t* smtm_live_ids(const smtm_ctx* ctx) { return ctx ? ctx->live[ctx->cur] : nullptr; }
 
 int32_t smtm_batch_results(smtm_ctx* ctx, int32_t* exit_layer, int32_t* label, int32_t* tier, void* stream) {
-    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (int32_t rc = check_ctx(ctx)) return rc;
     if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");
     hipStream_t st = static_cast<hipStream_t>(stream);
     launch_copy3_i32(ctx->res_layer, exit_layer, ctx->res_label, label, ctx->res_tier, tier, ctx->batch, st);
@@ -528,7 +553,7 @@ int32_t smtm_batch_results(smtm_ctx* ctx, int32_t* exit_layer, int32_t* label, i
 }
 
 int32_t smtm_read_counts(smtm_ctx* ctx, int32_t* n_live_host, int32_t* n_exit_host, void* stream) {
-    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (int32_t rc = check_ctx(ctx)) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     Counts c;
     HIP_TRY(ctx, hipMemcpyAsync(&c, ctx->counts, sizeof(Counts), hipMemcpyDeviceToHost, st));
@@ -539,7 +564,7 @@ int32_t smtm_read_counts(smtm_ctx* ctx, int32_t* n_live_host, int32_t* n_exit_ho
 }
 
 int32_t smtm_read_stats(smtm_ctx* ctx, int32_t* stats_host, void* stream) {
-    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (int32_t rc = check_ctx(ctx)) return rc;
     if (!stats_host) return fail(ctx, SMTM_ERR_INVALID_ARG, "stats_host is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
     Counts c;
@@ -566,7 +591,7 @@ static CentreTables centre_tables(const smtm_ctx* ctx) {
 }
 
 int32_t smtm_warmup_begin(smtm_ctx* ctx, void* stream) {
-    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (int32_t rc = check_ctx(ctx)) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int n = ctx->cfg.n_classes;
     for (int l = 0; l < ctx->cfg.n_exits; ++l) {
@@ -578,7 +603,7 @@ int32_t smtm_warmup_begin(smtm_ctx* ctx, void* stream) {
 }
 
 int32_t smtm_warmup_batch(smtm_ctx* ctx, const int32_t* label, int32_t batch, void* stream) {
-    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (int32_t rc = check_ctx(ctx)) return rc;
     if (!label) return fail(ctx, SMTM_ERR_INVALID_ARG, "label is NULL");
     if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");
     if (batch != ctx->batch) return fail(ctx, SMTM_ERR_SHAPE, "batch %d differs from the batch begun (%d)", batch, ctx->batch);
@@ -596,7 +621,7 @@ int32_t smtm_warmup_batch(smtm_ctx* ctx, const int32_t* label, int32_t batch, vo
 }
 
 int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* stop_layer, int32_t batch, void* stream) {
-    if (!ctx) return fail(nullptr, SMTM_ERR_INVALID_ARG, "context is NULL");
+    if (int32_t rc = check_ctx(ctx)) return rc;
     if ((label == nullptr) != (stop_layer == nullptr))
         return fail(ctx, SMTM_ERR_INVALID_ARG, "label and stop_layer must be given together (or both NULL)");
     if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");

@@ -174,9 +174,7 @@ def forward_cached(ctx, mods, img, bufs, bucket: int):
     for l in range(1, 5):
         x = mods[l](x)
         xv = nhwc(x)
-        ctx.encode_nhwc(l, xv)
-        ctx.lookup_exit(l, fmap_in=xv, fmap_out=bufs[l - 1],
-                        row_bytes=xv.shape[1] * xv.shape[2] * xv.shape[3] * 2)
+        ctx.stage_nhwc(l, xv, fmap_out=bufs[l - 1])
         n_live, _ = ctx.read_counts()
         live.append(n_live)
         if n_live == 0:

@@ -102,6 +102,7 @@ def load_library():
         "smtm_exit_compact": [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp],
         "smtm_lookup_exit": [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp],
         "smtm_stage": [vp, i32, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp],
+        "smtm_stage_nhwc": [vp, i32, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp],
         "smtm_batch_results": [vp, vp, vp, vp, vp],
         "smtm_read_counts": [vp, vp, vp, vp],
         "smtm_read_stats": [vp, vp, vp],
@@ -266,6 +267,17 @@ class Smtm:
         self._ck(self.lib.smtm_stage(self._h, exit, _ptr(fmap), dtype, H, W, _ptr(row_ids), _ptr(exit_ids),
                                      _ptr(exit_labels), _ptr(exit_tier), _ptr(n_exit_dev), _ptr(live_ids),
                                      _ptr(n_live_dev), _ptr(fmap_out), self._st(stream)))
+
+    def stage_nhwc(self, exit: int, fmap, row_ids=None, exit_ids=None, exit_labels=None, exit_tier=None,
+                   n_exit_dev=None, live_ids=None, n_live_dev=None, fmap_out=None, stream=None,
+                   dtype=None, H=None, W=None):
+        """fmap is [rows, H, W, C] (channels last)."""
+        if dtype is None:
+            dtype = _dtype_code(fmap)
+            H, W = fmap.shape[1], fmap.shape[2]
+        self._ck(self.lib.smtm_stage_nhwc(self._h, exit, _ptr(fmap), dtype, H, W, _ptr(row_ids), _ptr(exit_ids),
+                                          _ptr(exit_labels), _ptr(exit_tier), _ptr(n_exit_dev), _ptr(live_ids),
+                                          _ptr(n_live_dev), _ptr(fmap_out), self._st(stream)))
 
     def live_ids(self) -> int:
         """Device address of the context's current live list (int32)."""

@@ -808,6 +808,40 @@ def test_resnet50_channels_last_batch_matches_oracle_decisions():
     ctx.close()
 
 
+def test_stage_nhwc_is_encode_nhwc_plus_lookup_exit():
+    # the one-call form on channels-last maps runs the same kernels: bit-identical lists, results and rows
+    w = configs.RESNET18
+    cents = streams.centroids(w); ls = streams.labels(w)
+    fm = [f.permute(0, 2, 3, 1).contiguous() for f in streams.batch_feature_maps(w, cents, ls, 0, DEV)]
+    outs = []
+    for one_call in (False, True):
+        ctx = P.make_ctx(w, cents, ls.initial_hot)
+        ctx.begin_batch(w.batch)
+        keep = []
+        for l in range(1, w.n_exits + 1):
+            F = fm[l - 1]
+            i32 = dict(dtype=torch.int32, device=DEV)
+            lists = [torch.full((w.batch,), -7, **i32) for _ in range(4)] + [torch.zeros(1, **i32), torch.zeros(1, **i32)]
+            gathered = torch.zeros_like(F)
+            kw = dict(exit_ids=lists[0], exit_labels=lists[1], exit_tier=lists[2], live_ids=lists[3],
+                      n_exit_dev=lists[4], n_live_dev=lists[5], fmap_out=gathered)
+            if one_call:
+                ctx.stage_nhwc(l, F, row_ids=ctx.live_ids(), **kw)
+            else:
+                ids = ctx.live_ids()
+                ctx.encode_nhwc(l, F, row_ids=ids)
+                ctx.lookup_exit(l, fmap_in=F, row_ids=ids, row_bytes=F[0].numel() * 2, **kw)
+            keep += lists + [gathered.view(torch.int16)]
+        res = [torch.zeros(w.batch, dtype=torch.int32, device=DEV) for _ in range(3)]
+        ctx.batch_results(*res)
+        torch.cuda.synchronize()
+        outs.append([k.cpu() for k in keep + res])
+        ctx.close()
+    assert (outs[0][-3] > 0).any()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 # ------------------------------------------------------------------ workload 5 at its full length
 
 def test_adaptive_stream_full_length():
