@@ -160,20 +160,51 @@ def main() -> int:
     stage1_ms = float(np.median([a.elapsed_time(b) for a, b in sev]))
     stage1_bytes = B * per_exit_bytes[0]
 
+    # ---- the clean bandwidth case: an unreachable threshold, so every frame is live at every exit point
+    # (encode + lookup + exit/compact at all exit points; nothing to gather, nothing released)
+    ctx.set_tau(3.0e38)
+    nev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for r in range(reps):
+        nev[r][0].record()
+        ctx.begin_batch(B)
+        for l in range(1, L + 1):
+            ctx.encode(l, fmaps[l - 1], row_ids=ctx.live_ids())
+            ctx.lookup_exit(l)
+        nev[r][1].record()
+    torch.cuda.synchronize()
+    n_live_end, _ = ctx.read_counts()
+    assert n_live_end == B, "frames were released at an unreachable threshold"
+    ctx.set_tau(w.tau)
+    noexit_ms = float(np.median([a.elapsed_time(b) for a, b in nev]))
+    noexit_bytes = B * per_exit_bytes.sum()
+
     from oracle import smtm_oracle as O
     ns = min(args.cpu_sample, B)
     host = [f[:ns].cpu().numpy() for f in fmaps]
     cores = O.get_max_threads()
-    cpu_s = 0.0
-    for _ in range(args.cpu_reps):                       # the same batch each time, from a fresh memory
-        mem = O.Memory([c.numpy() for c in cents], ls.initial_hot, tau=w.tau, tiers=w.tiers, window=w.window,
-                       hot_min=cfg.hot_min, hot_max=hot_max, init_count=w.init_count)
-        t1 = time.perf_counter()
-        mem.begin_batch(ns)
-        for l in range(1, L + 1):
-            mem.stage(l, host[l - 1], row_ids=mem.live.copy())
-        mem.cache_update(mem.label, mem.exit_layer)
-        cpu_s += time.perf_counter() - t1
+
+    def oracle_seconds(frames: int, times: int) -> float:
+        total_s = 0.0
+        for _ in range(times):                           # the same frames each time, from a fresh memory
+            mem = O.Memory([c.numpy() for c in cents], ls.initial_hot, tau=w.tau, tiers=w.tiers, window=w.window,
+                           hot_min=cfg.hot_min, hot_max=hot_max, init_count=w.init_count)
+            t1 = time.perf_counter()
+            mem.begin_batch(frames)
+            for l in range(1, L + 1):
+                mem.stage(l, host[l - 1][:frames], row_ids=mem.live.copy())
+            mem.cache_update(mem.label, mem.exit_layer)
+            total_s += time.perf_counter() - t1
+        return total_s
+
+    cpu_s = oracle_seconds(ns, args.cpu_reps)
+    n1 = min(ns, 128)                                    # one thread: a smaller sample of the same frames
+    O.set_threads(1)
+    cpu1_s = oracle_seconds(n1, 1)
+    O.set_threads(cores)
+    try:
+        cpu_model = next(ln.split(":", 1)[1].strip() for ln in open("/proc/cpuinfo") if ln.startswith("model name"))
+    except (OSError, StopIteration):
+        cpu_model = "unknown"
 
     out = {
         "metric": "frames/sec through encode+lookup+exit (ResNet-50 exits)" if w.name == "resnet50"
@@ -192,7 +223,10 @@ def main() -> int:
                      "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "cpu_baseline": {"value": ns * args.cpu_reps / cpu_s, "unit": "frames/s", "cores": cores, "kind": "oracle",
                          "sample": f"first {ns} frames of the same batch, all {L} exit points and the memory "
-                                   f"update, {args.cpu_reps} times over: {cpu_s:.2f} s on {cores} threads"},
+                                   f"update, {args.cpu_reps} times over: {cpu_s:.2f} s on {cores} threads",
+                         "one_thread": {"value": n1 / cpu1_s, "sample": f"first {n1} frames, once: {cpu1_s:.2f} s"},
+                         "cpu": cpu_model, "host_cpus": os.cpu_count(),
+                         "gpu_over_oracle": fps / (ns * args.cpu_reps / cpu_s)},
         "encode_ms_per_exit_point": [None if np.isnan(x) else round(float(x), 4) for x in enc_ms.mean(axis=0)],
         "encode_gbs_per_exit_point": [None if np.isnan(t) else round(float(b / (t * 1e-3) / 1e9), 1)
                                       for b, t in zip(enc_bytes.mean(axis=0), enc_ms.mean(axis=0))],
@@ -200,6 +234,11 @@ def main() -> int:
         "exit1_stage": {"what": "encode + lookup + exit/compact of exit point 1 on the full batch, no gather",
                         "ms": stage1_ms, "GB/s": stage1_bytes / (stage1_ms * 1e-3) / 1e9,
                         "hbm_frac": stage1_bytes / (stage1_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "no_exit": {"what": "unreachable threshold: every frame live at every exit point; encode + lookup + "
+                            "exit/compact at all exit points, nothing to gather",
+                    "ms": noexit_ms, "frames/s": B / (noexit_ms * 1e-3),
+                    "GB/s": noexit_bytes / (noexit_ms * 1e-3) / 1e9,
+                    "hbm_frac": noexit_bytes / (noexit_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         # survivors after each exit point for every step run (warm-up included), so that per-dispatch
         # byte counts of a profile of this command can be reconstructed
         "survivors_log": live_log.cpu().numpy().tolist(),
