@@ -160,6 +160,7 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
     __shared__ int list[kListCap];
     __shared__ int w_cnt[4];
     __shared__ float red[4];
+    __shared__ float part[256];
     if (cls_cnt[j] == 0) return;                         // uniform over the block
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int C = tabs.C[l0], Cp = tabs.Cp[l0];
@@ -188,27 +189,67 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
     overflow = cnt > kListCap;
     const float m_old = (float)tabs.mcount[l0][j];
     float ss = 0.f;
-    // thread = channel (256 at a time, coalesced rows), frames of the list in ascending order,
-    // eight rows in flight
-    for (int c = tid; c < C; c += 256) {
+    // thread = channel (256 at a time, coalesced rows), frames of the list in ascending order, up to 32
+    // rows in flight.  Narrow layers (C <= 128) put 256 / Cw threads on each channel (Cw = C rounded
+    // up to a power of two): thread (g, c) adds the frames g, g + G, ... of the list and the G partial
+    // sums meet in LDS in the order of g, so the result does not depend on the launch.
+    int Cw = 256, G = 1;
+    if (C <= 128 && !overflow) {
+        Cw = 1;
+        while (Cw < C) Cw <<= 1;
+        G = 256 / Cw;
+    }
+    if (G > 1) {
+        const int g = tid / Cw, c = tid - g * Cw;
         float sum = 0.f;
-        if (!overflow) {
-            int i = 0;
-            for (; i + 8 <= cnt; i += 8) {
+        if (c < C) {
+            int i = g;
+            for (; i + 7 * G < cnt; i += 8 * G) {
                 float a[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) a[u] = sv[(int64_t)list[i + u] * C + c];
+                for (int u = 0; u < 8; ++u) a[u] = sv[(int64_t)list[i + u * G] * C + c];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) sum += a[u];
             }
-            for (; i < cnt; ++i) sum += sv[(int64_t)list[i] * C + c];
-        } else {                                         // more frames of one class than the list holds
-            for (int b = 0; b < batch; ++b)
-                if (label[b] == j && stop_layer[b] > l0) sum += sv[(int64_t)b * C + c];
+            for (; i < cnt; i += G) sum += sv[(int64_t)list[i] * C + c];
         }
-        const float x = (sc[c] * m_old + sum) / (m_old + (float)cnt);
-        sc[c] = x;
-        ss += x * x;
+        part[tid] = sum;
+        __syncthreads();
+        if (g == 0 && c < C) {
+            float tot = part[c];
+            for (int k = 1; k < G; ++k) tot += part[k * Cw + c];
+            const float x = (sc[c] * m_old + tot) / (m_old + (float)cnt);
+            sc[c] = x;
+            ss += x * x;
+        }
+    } else {
+        for (int c = tid; c < C; c += 256) {
+            float sum = 0.f;
+            if (!overflow) {
+                int i = 0;
+                for (; i + 32 <= cnt; i += 32) {
+                    float a[32];
+#pragma unroll
+                    for (int u = 0; u < 32; ++u) a[u] = sv[(int64_t)list[i + u] * C + c];
+#pragma unroll
+                    for (int u = 0; u < 32; ++u) sum += a[u];
+                }
+                for (; i + 8 <= cnt; i += 8) {
+                    float a[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) a[u] = sv[(int64_t)list[i + u] * C + c];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) sum += a[u];
+                }
+                for (; i < cnt; ++i) sum += sv[(int64_t)list[i] * C + c];
+            } else {                                     // more frames of one class than the list holds
+                for (int b = 0; b < batch; ++b)
+                    if (label[b] == j && stop_layer[b] > l0) sum += sv[(int64_t)b * C + c];
+            }
+            const float x = (sc[c] * m_old + sum) / (m_old + (float)cnt);
+            sc[c] = x;
+            ss += x * x;
+        }
     }
     for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
     if (lane == 0) red[wave] = ss;
