@@ -197,6 +197,52 @@ __global__ __launch_bounds__(256) void k_encode_pair(
 }
 
 // lds path.  Dynamic LDS: 4 wavefronts x (64 * HW * sizeof(T)) bytes, each a multiple of 16.
+// A wavefront owns its region and its tasks (64 channels of one frame): nothing is shared between
+// the wavefronts of a block, so they only order their own LDS traffic and never wait for each other.
+__device__ __forceinline__ void wave_lds_order() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Sum of the HW elements that start at element `first` of the wavefront's region.
+template <typename T>
+__device__ __forceinline__ float lds_channel_sum(const T* region, int first, int HW) {
+    if constexpr (sizeof(T) == 2) {
+        // two halves per 32-bit read; the first and the last word may belong to this channel only in part
+        const uint32_t* wq = reinterpret_cast<const uint32_t*>(region);
+        const int last = first + HW - 1;
+        const int w0 = first >> 1, w1 = last >> 1;
+        auto lo = [](uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xffffu)); };
+        auto hi = [](uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); };
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        uint32_t u = wq[w0];
+        if (first & 1) a1 += hi(u);
+        else { a0 += lo(u); if (first < last) a1 += hi(u); }
+        int w = w0 + 1;
+        for (; w + 2 <= w1; w += 2) {
+            const uint32_t p = wq[w], q = wq[w + 1];
+            a0 += lo(p); a1 += hi(p); a2 += lo(q); a3 += hi(q);
+        }
+        for (; w < w1; ++w) { const uint32_t p = wq[w]; a0 += lo(p); a1 += hi(p); }
+        if (w1 > w0) {
+            u = wq[w1];
+            a0 += lo(u);
+            if (last & 1) a1 += hi(u);
+        }
+        return (a0 + a1) + (a2 + a3);
+    } else {
+        const T* q = region + first;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        int i = 0;
+        for (; i + 4 <= HW; i += 4) {
+            a0 += (float)q[i]; a1 += (float)q[i + 1]; a2 += (float)q[i + 2]; a3 += (float)q[i + 3];
+        }
+        for (; i < HW; ++i) a0 += (float)q[i];
+        return (a0 + a1) + (a2 + a3);
+    }
+}
+
 template <typename T, int UNR>
 __global__ __launch_bounds__(256) void k_encode_lds(
     const T* __restrict__ F, const int32_t* __restrict__ row_ids,
@@ -207,58 +253,61 @@ __global__ __launch_bounds__(256) void k_encode_lds(
     const int wave = threadIdx.x >> 6;
     const int tile_bytes = 64 * HW * (int)sizeof(T);
     u32x4* my16 = lds16 + wave * (tile_bytes >> 4);
-    const T* myT = reinterpret_cast<const T*>(my16);
+    T* myT = reinterpret_cast<T*>(my16);
     const int gpf = (C + 63) >> 6;                       // 64-channel groups per frame
-    const int bpf = (gpf + 3) >> 2;                      // block tasks per frame
     int n_live = counts->n_live;
     if (n_live > max_rows) n_live = max_rows;
-    const int64_t total = (int64_t)n_live * bpf;
+    const int64_t total = (int64_t)n_live * gpf;
+    const int64_t n_waves = (int64_t)gridDim.x * 4;
 
-    for (int64_t t = blockIdx.x; t < total; t += gridDim.x) {    // uniform over the block
-        const int slot = (int)(t / bpf);
-        const int cg = (int)(t - (int64_t)slot * bpf) * 4 + wave;
-        const bool active = cg < gpf;
-        int nch = 0;
-        if (active) {
-            nch = C - cg * 64;
-            if (nch > 64) nch = 64;
-            const int64_t row = row_ids ? row_ids[slot] : slot;
-            const T* p = F + (row * C + (int64_t)cg * 64) * HW;
-            const int bytes = nch * HW * (int)sizeof(T);
-            const int nfull = bytes >> 4;
-            const u32x4* p16 = reinterpret_cast<const u32x4*>(p);
-            for (int base = 0; base < nfull; base += 64 * UNR) {
-                u32x4 v[UNR];
+    // The global loads of the next task are issued before the LDS pass over the current one, so a
+    // wavefront always has loads in flight.  The launcher picks UNR so that one round of UNR loads
+    // per lane covers a task: 64 * HW * sizeof(T) <= 64 * UNR * 16 bytes.
+    auto fetch = [&](int64_t t, u32x4 (&v)[UNR], T& tail, int& nfull, int& nch, int& slot, int& cg) {
+        slot = (int)(t / gpf);
+        cg = (int)(t - (int64_t)slot * gpf);
+        nch = C - cg * 64;
+        if (nch > 64) nch = 64;
+        const int64_t row = row_ids ? row_ids[slot] : slot;
+        const T* p = F + (row * C + (int64_t)cg * 64) * HW;
+        nfull = (nch * HW * (int)sizeof(T)) >> 4;
+        const u32x4* p16 = reinterpret_cast<const u32x4*>(p);
 #pragma unroll
-                for (int u = 0; u < UNR; ++u) {
-                    const int idx = base + u * 64 + lane;
-                    if (idx < nfull) v[u] = __builtin_nontemporal_load(p16 + idx);
-                }
+        for (int u = 0; u < UNR; ++u) {
+            const int idx = u * 64 + lane;
+            if (idx < nfull) v[u] = __builtin_nontemporal_load(p16 + idx);
+        }
+        const int done = (nfull << 4) / (int)sizeof(T);             // elements covered by whole chunks
+        const int rem = nch * HW - done;                            // < 16 / sizeof(T)
+        if (lane < rem) tail = p[done + lane];
+    };
+
+    u32x4 v[UNR];
+    T tail = (T)0;
+    int nfull = 0, nch = 0, slot = 0, cg = 0;
+    int64_t t = (int64_t)blockIdx.x * 4 + wave;                     // uniform over the wavefront
+    if (t < total) fetch(t, v, tail, nfull, nch, slot, cg);
+    while (t < total) {
 #pragma unroll
-                for (int u = 0; u < UNR; ++u) {
-                    const int idx = base + u * 64 + lane;
-                    if (idx < nfull) my16[idx] = v[u];
-                }
-            }
-            const int done = (nfull << 4) / (int)sizeof(T);         // elements covered by whole chunks
-            const int rem = nch * HW - done;                        // < 16 / sizeof(T)
-            if (lane < rem) const_cast<T*>(myT)[done + lane] = p[done + lane];
+        for (int u = 0; u < UNR; ++u) {
+            const int idx = u * 64 + lane;
+            if (idx < nfull) my16[idx] = v[u];
         }
-        __syncthreads();
-        if (active && lane < nch) {
-            const T* q = myT + lane * HW;
-            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-            int i = 0;
-            for (; i + 4 <= HW; i += 4) {
-                a0 += (float)q[i]; a1 += (float)q[i + 1]; a2 += (float)q[i + 2]; a3 += (float)q[i + 3];
-            }
-            for (; i < HW; ++i) a0 += (float)q[i];
-            const float m = ((a0 + a1) + (a2 + a3)) / (float)HW;
-            const int c = cg * 64 + lane;
-            sv[(int64_t)frame_ids[slot] * C + c] = m;
-            if (sv_out) sv_out[(int64_t)slot * C + c] = m;
+        {
+            const int done = (nfull << 4) / (int)sizeof(T);
+            if (lane < nch * HW - done) myT[done + lane] = tail;
         }
-        __syncthreads();
+        wave_lds_order();
+        const int cur_nch = nch, cur_slot = slot, cur_cg = cg;
+        t += n_waves;
+        if (t < total) fetch(t, v, tail, nfull, nch, slot, cg);
+        if (lane < cur_nch) {
+            const float m = lds_channel_sum<T>(myT, lane * HW, HW) / (float)HW;
+            const int c = cur_cg * 64 + lane;
+            sv[(int64_t)frame_ids[cur_slot] * C + c] = m;
+            if (sv_out) sv_out[(int64_t)cur_slot * C + c] = m;
+        }
+        wave_lds_order();
     }
 }
 
@@ -447,16 +496,22 @@ const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int3
     }
     if (frame_bytes % 16 == 0 && ch_bytes <= 256) {
         const int tile_bytes = 64 * (int)ch_bytes;                 // multiple of 16 since 64*esz is
-        const int gpf = (C + 63) / 64, bpf = (gpf + 3) / 4;
-        int grid = encode_grid((int64_t)max_rows * bpf, 1);
-        if (grid > 256 * 8) grid = 256 * 8;
+        const int gpf = (C + 63) / 64;
+        int grid = encode_grid((int64_t)max_rows * gpf, 4);
+        // as many blocks as stay resident at once (160 KB of LDS per CU, 8 blocks of 256 threads at most):
+        // each wavefront then walks several tasks and overlaps one task's sums with the next one's loads
+        int per_cu = (int)((160 * 1024) / ((size_t)tile_bytes * 4));
+        if (per_cu > 8) per_cu = 8;
+        if (per_cu < 1) per_cu = 1;
+        if (grid > 256 * per_cu) grid = 256 * per_cu;
         const size_t lds = (size_t)tile_bytes * 4;
-        if (dtype == SMTM_F16)
-            hipLaunchKernelGGL((k_encode_lds<_Float16, 8>), dim3(grid), dim3(256), lds, st,
-                               static_cast<const _Float16*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW);
-        else
-            hipLaunchKernelGGL((k_encode_lds<float, 8>), dim3(grid), dim3(256), lds, st,
-                               static_cast<const float*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW);
+        // one round of UNR 16-byte loads per lane has to cover a task (64 channels): 8 up to 128-byte channels, else 16
+#define SMTM_LAUNCH_LDS(T, UNR)                                                                              \
+        hipLaunchKernelGGL((k_encode_lds<T, UNR>), dim3(grid), dim3(256), lds, st, static_cast<const T*>(fmap), \
+                           row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW)
+        if (dtype == SMTM_F16) { if (ch_bytes <= 128) SMTM_LAUNCH_LDS(_Float16, 8); else SMTM_LAUNCH_LDS(_Float16, 16); }
+        else                   { if (ch_bytes <= 128) SMTM_LAUNCH_LDS(float, 8);    else SMTM_LAUNCH_LDS(float, 16); }
+#undef SMTM_LAUNCH_LDS
         return "lds";
     }
     if (ch_bytes % 4 == 0) {

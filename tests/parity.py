@@ -44,14 +44,34 @@ def rule_fp32(h, sh, tau):
     return bool(np.float32(h - sh) > np.float32(tau * runner))
 
 
-def in_band(h, sh, tau, l, delta):
-    """Frames whose metric is within the tolerance of the threshold may differ in decision."""
+def dot_scale(SV: np.ndarray, SC: np.ndarray) -> np.ndarray:
+    """a[i, j] = sum_c |v_c||c_c| / (|v||c|): the rounding-error scale of the cosine of row i of SV
+    with row j of SC (the similarity tolerance is rtol * max(|s|, a), and |s| <= a <= 1)."""
+    nv = np.linalg.norm(SV, axis=1)
+    nc = np.linalg.norm(SC, axis=1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        a = (np.abs(SV) @ np.abs(SC).T) / (nv[:, None] * nc[None, :])
+    a[~np.isfinite(a)] = 0.0
+    return a
+
+
+def in_band(h, sh, tau, l, delta, scale=None):
+    """Frames whose metric is within the tolerance of the threshold may differ in decision.
+
+    Every similarity may be off by delta * a, so an accumulated similarity of exit point l may be
+    off by delta * scale, scale = sum over the exit points so far of 2^(l'-1) * a (at most 2^l - 1,
+    the default).  The exit rule compares SA_H with (1 + tau) * max(SA_SH, 0): its two sides may
+    move by delta * scale * (2 + tau) against each other, and the sign of SA_H is uncertain while
+    |SA_H| <= delta * scale.  `scale` is the largest one over the tier's classes, because rounding
+    may also change which class is second."""
     if not np.isfinite(h) or not np.isfinite(sh):
         return False
+    if scale is None:
+        scale = 2.0 ** l - 1.0
     g = h - (1.0 + tau) * max(sh, 0.0)
-    if abs(g) <= delta * (abs(h) + (1.0 + tau) * abs(sh)):
+    if abs(g) <= delta * scale * (2.0 + tau):
         return True
-    return abs(h) <= delta * (2.0 ** l - 1.0)
+    return abs(h) <= delta * scale
 
 
 @dataclass
@@ -120,6 +140,7 @@ def check_batch(ctx: Smtm, mem: O.Memory, w: Workload, fmaps: List[torch.Tensor]
     live = np.arange(B, dtype=np.int32)
     if not rep.exit_hist:
         rep.exit_hist = [0] * (L + 1)
+    acc_scale = np.zeros((B, n), np.float64)            # per frame and class: sum of 2^(l-1) * a so far
 
     i32 = dict(dtype=torch.int32, device=dev)
     exit_ids = torch.full((B,), -7, **i32); exit_labels = torch.full((B,), -7, **i32)
@@ -236,17 +257,20 @@ def check_batch(ctx: Smtm, mem: O.Memory, w: Workload, fmaps: List[torch.Tensor]
 
         # ---- decisions and labels against the oracle, with the tolerance band
         rv = ref["top_val"]
+        acc_scale[live] += 2.0 ** (l - 1) * dot_scale(ref["SV"], mem.SC[l - 1])
+        scale1 = acc_scale[live][:, mem.hot_ids].max(axis=1) if n_live else np.zeros(0)
+        scale2 = acc_scale[live].max(axis=1) if n_live else np.zeros(0)
         for i in np.flatnonzero((dec_gpu != ref["decision"]) | (lab_gpu != ref["label"])):
-            band = in_band(rv[i, 0, 0], rv[i, 0, 1], tau, l, rtol) or \
-                (mem.tiers == 2 and in_band(rv[i, 1, 0], rv[i, 1, 1], tau, l, rtol))
+            band = in_band(rv[i, 0, 0], rv[i, 0, 1], tau, l, rtol, scale1[i]) or \
+                (mem.tiers == 2 and in_band(rv[i, 1, 0], rv[i, 1, 1], tau, l, rtol, scale2[i]))
             near_tie = any(abs(rv[i, t, 0] - rv[i, t, 1]) <= 2 * rtol * (2.0 ** l - 1.0) for t in range(2)
                            if np.isfinite(rv[i, t, 1]))
             assert band or near_tie, (f"exit {l} frame {live[i]}: decision/label {dec_gpu[i]}/{lab_gpu[i]} vs oracle "
                                       f"{ref['decision'][i]}/{ref['label'][i]} outside the tolerance band, top={rv[i]}")
             rep.in_band_flips += 1
         for i in range(n_live):
-            if in_band(rv[i, 0, 0], rv[i, 0, 1], tau, l, rtol) or \
-                    (mem.tiers == 2 and in_band(rv[i, 1, 0], rv[i, 1, 1], tau, l, rtol)):
+            if in_band(rv[i, 0, 0], rv[i, 0, 1], tau, l, rtol, scale1[i]) or \
+                    (mem.tiers == 2 and in_band(rv[i, 1, 0], rv[i, 1, 1], tau, l, rtol, scale2[i])):
                 rep.in_band_frames += 1
 
         # ---- gathered survivors: byte-identical rows

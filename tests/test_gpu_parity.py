@@ -57,6 +57,11 @@ ENCODE_SHAPES = [
     (torch.float32, 3, 5, 3, 3),       # 36-byte channels, 180-byte frames -> d4
     (torch.float32, 2, 6, 7, 6),       # 168-byte channels -> d8
     (torch.float16, 70, 64, 7, 7),     # more frames than one pass of a small grid
+    (torch.float32, 3, 72, 7, 7),      # lds fp32, 196-byte channels: the 16-loads-per-lane instance, group + tail
+    (torch.float16, 3, 80, 11, 11),    # lds fp16, 242-byte channels: the 16-loads-per-lane instance
+    (torch.float16, 3, 64, 1, 1),      # lds with one element per channel
+    (torch.float16, 3, 72, 1, 2),      # lds with one 32-bit word per channel
+    (torch.float16, 1100, 128, 7, 7),  # lds, several tasks per wavefront (the next task's loads overlap the sums)
 ]
 
 
@@ -266,7 +271,8 @@ def test_adaptive_partial_last_batch():
 def test_cache_update_random_tables():
     rng = np.random.default_rng(3)
     n, dims, B = 300, [24, 40], 700
-    cents = [torch.randn(n, c) for c in dims]
+    gc = torch.Generator().manual_seed(31)
+    cents = [torch.randn(n, c, generator=gc) for c in dims]
     w = dataclasses.replace(configs.ADAPTIVE, n_classes=n, exits=((24, 2, 2), (40, 2, 2)), batch=B, hot=10,
                             hot_min=5, hot_max=200, window=50, init_count=3)
     hot0 = np.arange(10, dtype=np.int32)
@@ -294,7 +300,7 @@ def test_cache_update_saturating_tables_and_big_scores():
     n = 64
     w = dataclasses.replace(configs.ADAPTIVE, n_classes=n, exits=((8, 1, 1),), batch=16, hot=4, hot_min=2,
                             hot_max=n, window=7)
-    cents = [torch.randn(n, 8)]
+    cents = [torch.randn(n, 8, generator=torch.Generator().manual_seed(32))]
     ctx = P.make_ctx(w, cents, np.arange(4, dtype=np.int32))
     mem = P.make_oracle(w, cents, np.arange(4, dtype=np.int32))
     ft = np.full(n, 2 ** 32 - 3, np.uint32); ts = np.zeros(n, np.uint32)
@@ -549,7 +555,7 @@ def test_cache_update_forgetting_in_place(window):
     n = 120
     w = dataclasses.replace(configs.ADAPTIVE, n_classes=n, exits=((16, 1, 1),), batch=900, hot=10, hot_min=4,
                             hot_max=100, window=window)
-    cents = [torch.randn(n, 16)]
+    cents = [torch.randn(n, 16, generator=torch.Generator().manual_seed(33))]
     hot0 = np.arange(10, dtype=np.int32)
     ctx = P.make_ctx(w, cents, hot0, forgetting=1)
     mem = P.make_oracle(w, cents, hot0, forgetting=1)
@@ -577,7 +583,7 @@ def test_frame_by_frame_cadence_equals_one_batch(forgetting):
     n, B = 60, 150
     w = dataclasses.replace(configs.ADAPTIVE, n_classes=n, exits=((8, 1, 1),), batch=B, hot=6, hot_min=3,
                             hot_max=50, window=9)
-    cents = [torch.randn(n, 8)]
+    cents = [torch.randn(n, 8, generator=torch.Generator().manual_seed(32))]
     hot0 = np.arange(6, dtype=np.int32)
     label = np.where(rng.random(B) < 0.1, -1, np.minimum(rng.zipf(1.3, B) - 1, n - 1)).astype(np.int32)
     a = P.make_ctx(w, cents, hot0, forgetting=forgetting)
