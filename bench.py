@@ -227,6 +227,49 @@ def main() -> int:
             lane["ctx"].close()
         del lanes
 
+    # ---- one frame at a time (the paper's own cadence): a batch of one through every exit point and the
+    # memory update, recorded once in a HIP graph and replayed.  Informational: latency, not throughput.
+    one_frame_us = None
+    if not args.skip_extras:
+        try:
+            c1 = Smtm(SmtmConfig(n_classes=n, dims=w.dims, max_batch=1, hot_init=w.hot,
+                                 hot_min=w.hot_min if w.hot_max else w.hot, hot_max=hot_max, tiers=w.tiers,
+                                 tau=w.tau, window=w.window, init_count=w.init_count))
+            for l, c in enumerate(cents, start=1):
+                c1.memory_load(l, c.numpy())
+            c1.hot_set(ls.initial_hot)
+            one = [f[:1].clone() for f in fmaps]
+
+            def one_step():
+                c1.begin_batch(1)
+                for l in range(1, L + 1):
+                    c1.encode(l, one[l - 1], row_ids=c1.live_ids())
+                    c1.lookup_exit(l)
+                c1.cache_update(None, None, 1)
+
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                one_step()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                one_step()
+            for _ in range(5):
+                graph.replay()
+            torch.cuda.synchronize()
+            t3 = time.perf_counter()
+            n_rep = 200
+            for _ in range(n_rep):
+                graph.replay()
+            torch.cuda.synchronize()
+            one_frame_us = (time.perf_counter() - t3) / n_rep * 1e6
+            del graph
+            c1.close()
+        except Exception as e:                               # reported, never fatal for the main figure
+            print(f"bench.py: single-frame graph run skipped: {e}", file=sys.stderr)
+
     from oracle import smtm_oracle as O
     ns = min(args.cpu_sample, B)
     host = [f[:ns].cpu().numpy() for f in fmaps]
@@ -290,6 +333,8 @@ def main() -> int:
                     "hbm_frac": noexit_bytes / (noexit_ms * 1e-3) / 1e9 / HBM_PEAK_GBS} if noexit_clean else None,
         "two_contexts": {"what": "two independent frame streams (two contexts, own memory and tensors) on two HIP "
                                  "streams, same step each; aggregate", "frames/s": two_fps} if two_fps else None,
+        "one_frame": {"what": "batch of one through every exit point and the memory update, replayed from a HIP "
+                              "graph; microseconds per frame", "us": one_frame_us} if one_frame_us else None,
         # survivors after each exit point for every step run (warm-up included), so that per-dispatch
         # byte counts of a profile of this command can be reconstructed
         "survivors_log": live_log.cpu().numpy().tolist(),

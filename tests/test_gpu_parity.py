@@ -524,8 +524,8 @@ def test_step_captured_in_a_graph_replays_like_eager():
     graph_ctx, graph_bufs = make()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):                 # the live-list pointers alternate every exit point: with an
-        step(graph_ctx, graph_bufs)               # even number of exit points a step starts where it began
+    with torch.cuda.stream(side):                 # every batch starts on the first of the two live lists, so the
+        step(graph_ctx, graph_bufs)               # pointers recorded in the graph are those of every later step
     torch.cuda.current_stream().wait_stream(side)
     step(eager_ctx, eager_bufs)
     torch.cuda.synchronize()
