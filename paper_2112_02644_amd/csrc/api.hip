@@ -412,6 +412,7 @@ static CompactArgs compact_args(smtm_ctx* ctx, int32_t exit, int32_t* exit_ids, 
     CompactArgs a;
     a.decision = ctx->decision; a.label = ctx->dlabel; a.frame_ids = ctx->live[ctx->cur];
     a.next_ids = ctx->live[ctx->cur ^ 1]; a.next_slots = ctx->next_slots; a.counts = ctx->counts;
+    a.max_rows = ctx->batch;
     a.exit_index = exit;
     a.exit_ids = exit_ids; a.exit_labels = exit_labels; a.exit_tier = exit_tier; a.n_exit_dev = n_exit_dev;
     a.live_ids_user = live_ids; a.n_live_dev = n_live_dev;

@@ -40,17 +40,28 @@ void launch_begin_batch(float* SA, int n, int batch, int32_t* live, int32_t* res
 // Stable partition of the live list by one block: wavefront ballot + popcount prefix, an LDS scan
 // over the block's wavefronts, running bases across chunks of the list.
 template <int NW>                                        // wavefronts in the block
-__device__ __forceinline__ void compact_block(const CompactArgs& a, int n_live) {
+__device__ __forceinline__ void compact_block(const CompactArgs& a) {
     __shared__ int w_exit[NW], w_t1[NW];
     __shared__ int base_exit, base_t1;
     constexpr int BS = NW * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // The first chunk's entries are fetched together with the live count (all of it was written by the
+    // kernel before; fetched one after the other it would cost three round trips).  The lists have
+    // max_rows entries.
+    int n_live = a.counts->n_live;
+    int d0 = 0, frame0 = 0, lab0 = -1;
+    if (tid < a.max_rows) { d0 = a.decision[tid]; frame0 = a.frame_ids[tid]; lab0 = a.label[tid]; }
+    asm volatile("" : "+v"(d0), "+v"(frame0), "+v"(lab0), "+s"(n_live));   // issued before any is waited for
     if (tid == 0) { base_exit = 0; base_t1 = 0; }
     __syncthreads();
     for (int c0 = 0; c0 < n_live; c0 += BS) {            // uniform over the block
         const int slot = c0 + tid;
         const bool valid = slot < n_live;
-        const int d = valid ? a.decision[slot] : 0;
+        int d = 0, frame = 0, lab = -1;
+        if (valid) {
+            if (c0 == 0) { d = d0; frame = frame0; lab = lab0; }
+            else { d = a.decision[slot]; frame = a.frame_ids[slot]; lab = a.label[slot]; }
+        }
         const bool ex = valid && d != 0;
         const unsigned long long m_ex = __ballot(ex);
         const unsigned long long m_t1 = __ballot(valid && d == 1);
@@ -66,10 +77,8 @@ __device__ __forceinline__ void compact_block(const CompactArgs& a, int n_live) 
         }
         const int be = base_exit;
         if (valid) {
-            const int frame = a.frame_ids[slot];
             if (ex) {
                 const int pos = be + off_ex + pre_ex;
-                const int lab = a.label[slot];
                 if (a.exit_ids) a.exit_ids[pos] = frame;
                 if (a.exit_labels) a.exit_labels[pos] = lab;
                 if (a.exit_tier) a.exit_tier[pos] = d;
@@ -100,7 +109,7 @@ __device__ __forceinline__ void compact_block(const CompactArgs& a, int n_live) 
 
 // One block of 1024 threads (16 wavefronts) walks the live list in chunks of 1024 slots.
 __global__ __launch_bounds__(1024) void k_compact(CompactArgs a) {
-    compact_block<16>(a, a.counts->n_live);
+    compact_block<16>(a);
 }
 
 void launch_compact(const CompactArgs& args, hipStream_t st) {

@@ -26,6 +26,7 @@ struct CompactArgs {                      // everything the stable partition rea
     int32_t* next_ids;                    // survivors' frame ids (the next live list)
     int32_t* next_slots;                  // survivors' old slots (for the row gather)
     Counts* counts;
+    int max_rows;                         // entries in the lists above (the batch begun)
     int exit_index;                       // 1-based
     int32_t *exit_ids, *exit_labels, *exit_tier, *n_exit_dev, *live_ids_user, *n_live_dev;   // caller's, may be NULL
     int32_t *res_layer, *res_label, *res_tier;                                               // per-frame results

@@ -69,12 +69,18 @@ __global__ __launch_bounds__(256) void k_rownorm(const float* __restrict__ sv,
                                                  float* __restrict__ vinv, _Float16* __restrict__ vhat,
                                                  int Cp) {
     const int lane = threadIdx.x & 63;
+    int slot = blockIdx.x * 4 + (threadIdx.x >> 6);
+    // The first slot's frame id is fetched together with the live count: both come from memory written by
+    // the kernel before, and one after the other they would cost two round trips.  The list has max_rows
+    // entries, all of them frame ids of this or an earlier batch.
     int n_live = counts->n_live;
+    int fid = slot < max_rows ? frame_ids[slot] : 0;
+    asm volatile("" : "+v"(fid), "+s"(n_live));          // both loads are issued before either is waited for
     if (n_live > max_rows) n_live = max_rows;
     const int n_waves = gridDim.x * 4;
     const bool vec = (C & 3) == 0;
-    for (int slot = blockIdx.x * 4 + (threadIdx.x >> 6); slot < n_live; slot += n_waves) {
-        const float* p = sv + (int64_t)frame_ids[slot] * C;
+    for (; slot < n_live; slot += n_waves, fid = slot < n_live ? frame_ids[slot] : 0) {
+        const float* p = sv + (int64_t)fid * C;
         float ss = 0.f;
         if (vec) {
             const f32x4* p4 = reinterpret_cast<const f32x4*>(p);
@@ -270,25 +276,35 @@ __global__ __launch_bounds__(256) void k_score_mfma(
     // issued before the live count is waited for
     fetch(ra0, rb0, 0);
     if (n_stage > 1) fetch(ra1, rb1, 1);
+    // Frame ids of this thread's output rows, then the old SA values of its outputs: two batches of
+    // loads (all ids, then all values) that complete under the K loop.  Indices are clamped into the
+    // buffers so that no load sits behind a branch (one behind a branch waits for the one before it,
+    // and sixteen such pairs in a row cost more than the whole contraction); the list holds max_rows
+    // frame ids of this or an earlier batch, so every address is inside SA, and what is fetched for
+    // rows or classes outside the live tile is never used.
+    int fid[WM][16];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int slot = m0 + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            fid[i][e] = frame_ids[slot < max_rows ? slot : max_rows - 1];
+        }
     int n_live = counts->n_live;
     if (n_live > max_rows) n_live = max_rows;
     if (m0 >= n_live) return;                            // uniform over the block
     stash(ra0, rb0, 0);
     __syncthreads();
 
-    // old SA values of this thread's outputs, fetched while the K loop runs
     float sa_old[WM][WN][16];
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             const int cls = n0 + (wn * WN + j) * 32 + (lane & 31);
+            const int cc = cls < n ? cls : n - 1;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int slot = m0 + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                sa_old[i][j][e] = 0.f;
-                if (slot < n_live && cls < n) sa_old[i][j][e] = SA[(int64_t)frame_ids[slot] * n + cls];
-            }
+            for (int e = 0; e < 16; ++e) sa_old[i][j][e] = SA[(int64_t)fid[i][e] * n + cc];
         }
 
     for (int st = 0; st < n_stage; st += 2) {            // two stages per trip so the register sets are static
@@ -315,8 +331,7 @@ __global__ __launch_bounds__(256) void k_score_mfma(
                 const int slot = m0 + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
                 if (slot < n_live && cls < n) {
                     const float s = acc[i][j][e];
-                    const int64_t frame = frame_ids[slot];
-                    SA[frame * n + cls] = sa_old[i][j][e] + weight * s;
+                    SA[(int64_t)fid[i][e] * n + cls] = sa_old[i][j][e] + weight * s;
                     if (sims_out) sims_out[(int64_t)slot * n + cls] = s;
                 }
             }
@@ -338,31 +353,28 @@ struct Top2 {
     float v1; int id1; float v2;
 };
 
-__device__ __forceinline__ bool better(float v, int id, float w, int jd) {
-    // (larger value first, then smaller class id); id < 0 marks "no entry"
-    if (jd < 0) return id >= 0;
-    if (id < 0) return false;
-    return v > w || (v == w && id < jd);
+// The order is (larger value first, then smaller class id); id < 0 with value -inf marks "no entry".
+// Accumulated similarities are finite, so -inf never is a real entry.  Everything below is written with
+// selects: as nested branches the per-element update cost several times the memory traffic of the row.
+
+// One more entry for a lane's running top-2.  A lane meets its classes in ascending id, so an equal value
+// never displaces the best one (strict >).  `take` = false leaves the triple as it is.
+__device__ __forceinline__ void top2_push(Top2& t, float v, int id, bool take = true) {
+    const float x = take ? v : -__builtin_inff();
+    const bool gt = x > t.v1;
+    t.v2 = gt ? t.v1 : fmaxf(t.v2, x);
+    t.id1 = gt ? id : t.id1;
+    t.v1 = gt ? x : t.v1;
 }
 
-__device__ __forceinline__ void top2_push(Top2& t, float v, int id) {
-    if (better(v, id, t.v1, t.id1)) {
-        if (t.id1 >= 0) t.v2 = t.v1;
-        t.v1 = v; t.id1 = id;
-    } else if (v > t.v2) {
-        t.v2 = v;
-    }
-}
-
+// Merge of another lane's (best, id, second) triple; the second of a triple never exceeds its best.
 __device__ __forceinline__ void top2_merge(Top2& t, float v1, int id1, float v2) {
-    // merge another (best, id, second) triple; the second of a triple never exceeds its best
-    if (better(v1, id1, t.v1, t.id1)) {
-        const float loser = t.id1 >= 0 ? t.v1 : -__builtin_inff();
-        t.v2 = fmaxf(v2, loser);
-        t.v1 = v1; t.id1 = id1;
-    } else if (id1 >= 0) {
-        t.v2 = fmaxf(t.v2, v1);
-    }
+    // ids compare as unsigned so that "no entry" (-1) loses a tie of two -inf against nothing real
+    const bool b = (v1 > t.v1) | ((v1 == t.v1) & ((uint32_t)id1 < (uint32_t)t.id1));
+    const float loser = b ? t.v1 : v1;
+    t.v2 = fmaxf(fmaxf(t.v2, v2), loser);
+    t.v1 = b ? v1 : t.v1;
+    t.id1 = b ? id1 : t.id1;
 }
 
 __device__ __forceinline__ bool exit_rule(float h, float sh, float tau) {
@@ -379,13 +391,16 @@ __global__ __launch_bounds__(256) void k_top2_decide(
     float* __restrict__ top_val, int32_t* __restrict__ top_id, float* __restrict__ top_val_user,
     int32_t* __restrict__ top_id_user) {
     const int lane = threadIdx.x & 63;
+    int slot = blockIdx.x * 4 + (threadIdx.x >> 6);
     int n_live = counts->n_live;
+    int fid = slot < max_rows ? frame_ids[slot] : 0;      // fetched together with the live count, as in k_rownorm
+    asm volatile("" : "+v"(fid), "+s"(n_live));
     if (n_live > max_rows) n_live = max_rows;
     const int n_waves = gridDim.x * 4;
     const float ninf = -__builtin_inff();
     const bool vec = (n & 3) == 0;
-    for (int slot = blockIdx.x * 4 + (threadIdx.x >> 6); slot < n_live; slot += n_waves) {
-        const float* row = SA + (int64_t)frame_ids[slot] * n;
+    for (; slot < n_live; slot += n_waves, fid = slot < n_live ? frame_ids[slot] : 0) {
+        const float* row = SA + (int64_t)fid * n;
         Top2 hot = {ninf, -1, ninf}, all = {ninf, -1, ninf};
         if (vec) {
             // each lane takes 4 consecutive classes per access, four accesses in flight
@@ -407,7 +422,7 @@ __global__ __launch_bounds__(256) void k_top2_decide(
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             top2_push(all, x[u][e], 4 * q + e);
-                            if ((h[u] >> (8 * e)) & 0xffu) top2_push(hot, x[u][e], 4 * q + e);
+                            top2_push(hot, x[u][e], 4 * q + e, ((h[u] >> (8 * e)) & 0xffu) != 0);
                         }
                     }
                 }
@@ -416,7 +431,7 @@ __global__ __launch_bounds__(256) void k_top2_decide(
             for (int j = lane; j < n; j += 64) {
                 const float x = row[j];
                 top2_push(all, x, j);
-                if (in_hot[j]) top2_push(hot, x, j);
+                top2_push(hot, x, j, in_hot[j] != 0);
             }
         }
         for (int off = 32; off > 0; off >>= 1) {
@@ -464,7 +479,7 @@ __global__ __launch_bounds__(256) void k_separability(const float* __restrict__ 
         for (int j = lane; j < n; j += 64) {
             const float x = row[j];
             top2_push(all, x, j);
-            if (in_hot[j]) top2_push(hot, x, j);
+            top2_push(hot, x, j, in_hot[j] != 0);
         }
         for (int off = 32; off > 0; off >>= 1) {
             float v1 = __shfl_xor(all.v1, off, 64); int id1 = __shfl_xor(all.id1, off, 64);
