@@ -18,7 +18,10 @@ __global__ __launch_bounds__(256) void k_begin_batch(float* __restrict__ SA, int
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t total = (int64_t)batch * n;
-    for (int64_t i = tid; i < total; i += stride) SA[i] = 0.f;
+    const int64_t quads = total >> 2;                    // SA comes from hipMalloc: 16-byte stores are aligned
+    u32x4* SA4 = reinterpret_cast<u32x4*>(SA);
+    for (int64_t i = tid; i < quads; i += stride) SA4[i] = u32x4{0u, 0u, 0u, 0u};
+    for (int64_t i = (quads << 2) + tid; i < total; i += stride) SA[i] = 0.f;
     for (int64_t i = tid; i < batch; i += stride) {
         live[i] = (int32_t)i;
         res_layer[i] = 0; res_label[i] = -1; res_tier[i] = 0;
@@ -30,8 +33,8 @@ __global__ __launch_bounds__(256) void k_begin_batch(float* __restrict__ SA, int
 void launch_begin_batch(float* SA, int n, int batch, int32_t* live, int32_t* res_layer,
                         int32_t* res_label, int32_t* res_tier, Counts* counts, hipStream_t st) {
     int64_t total = (int64_t)batch * n;
-    int grid = (int)((total + 1023) / 1024);
-    if (grid > 1024) grid = 1024;
+    int grid = (int)((total + 4095) / 4096);             // 256 threads x 16 bytes x 4 per block
+    if (grid > 2048) grid = 2048;
     if (grid < 1) grid = 1;
     hipLaunchKernelGGL(k_begin_batch, dim3(grid), dim3(256), 0, st, SA, n, batch, live, res_layer,
                        res_label, res_tier, counts);

@@ -82,6 +82,37 @@ __global__ __launch_bounds__(256) void k_rownorm(const float* __restrict__ sv,
     for (; slot < n_live; slot += n_waves, fid = slot < n_live ? frame_ids[slot] : 0) {
         const float* p = sv + (int64_t)fid * C;
         float ss = 0.f;
+        if (vec && Cp <= 2048) {
+            // the row stays in registers between the norm and the fp16 copy (at most 8 x 16 bytes per lane)
+            const f32x4* p4 = reinterpret_cast<const f32x4*>(p);
+            const int nq = C >> 2, nqp = Cp >> 2;           // Cp is a multiple of 64
+            f32x4 x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int q = u * 64 + lane;
+                x[u] = q < nq ? p4[q] : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                ss += (x[u].x * x[u].x + x[u].y * x[u].y) + (x[u].z * x[u].z + x[u].w * x[u].w);
+            ss = wave_sum(ss);
+            const float inv = inv_norm_of(ss);
+            if (lane == 0) vinv[slot] = inv;
+            if (vhat) {
+                _Float16* out = vhat + (int64_t)slot * Cp;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int q = u * 64 + lane;
+                    if (q < nqp) {
+                        f32x4 y = {0.f, 0.f, 0.f, 0.f};     // a zero or non-finite row (inv = 0) becomes zeros, as the padding
+                        if (inv != 0.f) y = x[u] * inv;
+                        const half4_t h = {(_Float16)y.x, (_Float16)y.y, (_Float16)y.z, (_Float16)y.w};
+                        *reinterpret_cast<half4_t*>(out + 4 * q) = h;
+                    }
+                }
+            }
+            continue;
+        }
         if (vec) {
             const f32x4* p4 = reinterpret_cast<const f32x4*>(p);
             const int nq = C >> 2;
@@ -238,9 +269,11 @@ __global__ __launch_bounds__(256) void k_score_mfma(
     const _Float16* a_src = A + (int64_t)(m0 + ld_row) * Cp + ld_chunk * 8;
     const _Float16* b_src = B + (int64_t)(n0 + ld_row) * Cp + ld_chunk * 8;
     const int lds_off = ld_row * MF_LD + ld_chunk * 8;
-    // Two register sets: while stage st is multiplied out of LDS, the loads of stage st+2 are in
-    // flight and stage st+1 (loaded one iteration earlier) is written to the other LDS buffer.
-    u32x4 ra0[RA], rb0[RB], ra1[RA], rb1[RB];
+    // Four register sets: while stage st is multiplied out of LDS, the loads of stages st+2 .. st+4 are
+    // in flight and stage st+1 (loaded three iterations earlier) is written to the other LDS buffer.
+    // A stage is 16 KB per block from L2 or beyond; with fewer stages in flight the K loop runs at the
+    // pace of that latency.
+    u32x4 ra0[RA], rb0[RB], ra1[RA], rb1[RB], ra2[RA], rb2[RB], ra3[RA], rb3[RB];
     const int n_stage = Cp / MF_K;
     auto fetch = [&](u32x4* ra, u32x4* rb, int stage) {
         const int k1 = stage * MF_K;
@@ -276,6 +309,8 @@ __global__ __launch_bounds__(256) void k_score_mfma(
     // issued before the live count is waited for
     fetch(ra0, rb0, 0);
     if (n_stage > 1) fetch(ra1, rb1, 1);
+    if (n_stage > 2) fetch(ra2, rb2, 2);
+    if (n_stage > 3) fetch(ra3, rb3, 3);
     // Frame ids of this thread's output rows, then the old SA values of its outputs: two batches of
     // loads (all ids, then all values) that complete under the K loop.  Indices are clamped into the
     // buffers so that no load sits behind a branch (one behind a branch waits for the one before it,
@@ -307,17 +342,29 @@ __global__ __launch_bounds__(256) void k_score_mfma(
             for (int e = 0; e < 16; ++e) sa_old[i][j][e] = SA[(int64_t)fid[i][e] * n + cc];
         }
 
-    for (int st = 0; st < n_stage; st += 2) {            // two stages per trip so the register sets are static
-        // even stage: LDS buffer 0 holds it, set 1 holds stage st+1
-        if (st + 2 < n_stage) fetch(ra0, rb0, st + 2);
+    for (int st = 0; st < n_stage; st += 4) {            // four stages per trip so the register sets are static
+        // stage st: LDS buffer 0 holds it; set 0 is free, sets 1..3 hold stages st+1 .. st+3
+        if (st + 4 < n_stage) fetch(ra0, rb0, st + 4);
         multiply(0);
         if (st + 1 < n_stage) stash(ra1, rb1, 1);        // buffer 1 was last read before the previous barrier
         __syncthreads();
         if (st + 1 >= n_stage) break;                    // uniform
-        // odd stage: LDS buffer 1 holds it, set 0 holds stage st+2
-        if (st + 3 < n_stage) fetch(ra1, rb1, st + 3);
+        // stage st+1: buffer 1
+        if (st + 5 < n_stage) fetch(ra1, rb1, st + 5);
         multiply(1);
-        if (st + 2 < n_stage) stash(ra0, rb0, 0);
+        if (st + 2 < n_stage) stash(ra2, rb2, 0);
+        __syncthreads();
+        if (st + 2 >= n_stage) break;
+        // stage st+2: buffer 0
+        if (st + 6 < n_stage) fetch(ra2, rb2, st + 6);
+        multiply(0);
+        if (st + 3 < n_stage) stash(ra3, rb3, 1);
+        __syncthreads();
+        if (st + 3 >= n_stage) break;
+        // stage st+3: buffer 1
+        if (st + 7 < n_stage) fetch(ra3, rb3, st + 7);
+        multiply(1);
+        if (st + 4 < n_stage) stash(ra0, rb0, 0);
         __syncthreads();
     }
 
