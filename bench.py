@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
 # profiles/encode_direct_f16_hbm_traffic.txt (same command, same workload).  Reported only while the kernel's
 # source is the one the counters were taken on; otherwise the field is null.
-TRAFFIC = {"workload": "resnet50", "bytes_per_launch": 1645843389.0,
+TRAFFIC = {"workload": "resnet50", "bytes_per_launch": 1645828444.0,
            "encode_sha256": "5412720ea5dd207b82c8feb0465be56284d2b31d72864910fe2ceec421ad6931"}
 
 
