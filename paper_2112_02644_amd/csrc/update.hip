@@ -211,7 +211,16 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
 #pragma unroll
                 for (int u = 0; u < 8; ++u) sum += a[u];
             }
-            for (; i < cnt; i += G) sum += sv[(int64_t)list[i] * C + c];
+            if (i < cnt) {                               // the rest (fewer than 8 of this group) in one batch
+                float a[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int k = i + u * G;
+                    a[u] = sv[(int64_t)list[k < cnt ? k : i] * C + c];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sum += i + u * G < cnt ? a[u] : 0.f;
+            }
         }
         part[tid] = sum;
         __syncthreads();
@@ -234,14 +243,21 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
 #pragma unroll
                     for (int u = 0; u < 32; ++u) sum += a[u];
                 }
-                for (; i + 8 <= cnt; i += 8) {
+                // the rest (fewer than 32 frames) in one batch: indices past the end are clamped and their
+                // values dropped, so the loads need no branch and the order of the additions stays the list's
+                if (cnt - i > 8) {
+                    float a[32];
+#pragma unroll
+                    for (int u = 0; u < 32; ++u) a[u] = sv[(int64_t)list[i + u < cnt ? i + u : i] * C + c];
+#pragma unroll
+                    for (int u = 0; u < 32; ++u) sum += i + u < cnt ? a[u] : 0.f;
+                } else if (cnt > i) {
                     float a[8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) a[u] = sv[(int64_t)list[i + u] * C + c];
+                    for (int u = 0; u < 8; ++u) a[u] = sv[(int64_t)list[i + u < cnt ? i + u : i] * C + c];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) sum += a[u];
+                    for (int u = 0; u < 8; ++u) sum += i + u < cnt ? a[u] : 0.f;
                 }
-                for (; i < cnt; ++i) sum += sv[(int64_t)list[i] * C + c];
             } else {                                     // more frames of one class than the list holds
                 for (int b = 0; b < batch; ++b)
                     if (label[b] == j && stop_layer[b] > l0) sum += sv[(int64_t)b * C + c];
