@@ -8,6 +8,7 @@
 namespace smtm {
 
 typedef unsigned __int128 u128;
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint64_t score_of(uint32_t ft, uint32_t ts, uint32_t W) {
     // Eq. 5 scaled by 4^15: FT * 4^(15 - min(floor(TS / W), 15)), exact in 64 bits
@@ -167,20 +168,45 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
     float* sc = tabs.centres[l0] + (int64_t)j * C;
     const float* sv = tabs.sv[l0];
 
-    // frames of this class that reached this exit point, ascending
+    // frames of this class that reached this exit point, ascending.  A thread looks at four consecutive
+    // frames per pass (one 16-byte load from each array when they are aligned), so a batch of 1024 is one
+    // pass; its hits go behind those of the lower lanes and wavefronts, which keeps the list in frame order.
     int cnt = 0;
     bool overflow = false;
-    for (int b0 = 0; b0 < batch; b0 += 256) {            // uniform trip count
-        const int b = b0 + tid;
-        const bool hit = b < batch && label[b] == j && stop_layer[b] > l0;
-        const unsigned long long m = __ballot(hit);
-        if (lane == 0) w_cnt[wave] = __popcll(m);
+    const bool vec_ok = ((reinterpret_cast<uintptr_t>(label) | reinterpret_cast<uintptr_t>(stop_layer)) & 15u) == 0;
+    for (int b0 = 0; b0 < batch; b0 += 1024) {           // uniform trip count
+        const int b = b0 + 4 * tid;
+        int lab[4] = {-1, -1, -1, -1}, stp[4] = {0, 0, 0, 0};
+        if (vec_ok && b + 3 < batch) {
+            const i32x4 lv = *reinterpret_cast<const i32x4*>(label + b);
+            const i32x4 sv4 = *reinterpret_cast<const i32x4*>(stop_layer + b);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { lab[k] = lv[k]; stp[k] = sv4[k]; }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (b + k < batch) { lab[k] = label[b + k]; stp[k] = stop_layer[b + k]; }
+        }
+        bool hit[4];
+        int pre = 0, tot_w = 0, own = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            hit[k] = lab[k] == j && stp[k] > l0;
+            const unsigned long long m = __ballot(hit[k]);
+            pre += __popcll(m & ((1ull << lane) - 1ull));
+            tot_w += __popcll(m);
+        }
+        if (lane == 0) w_cnt[wave] = tot_w;
         __syncthreads();
         int off = 0, tot = 0;
         for (int w = 0; w < 4; ++w) { if (w < wave) off += w_cnt[w]; tot += w_cnt[w]; }
-        if (hit) {
-            const int pos = cnt + off + __popcll(m & ((1ull << lane) - 1ull));
-            if (pos < kListCap) list[pos] = b;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (hit[k]) {
+                const int pos = cnt + off + pre + own;
+                if (pos < kListCap) list[pos] = b + k;
+                ++own;
+            }
         }
         cnt += tot;
         __syncthreads();
