@@ -303,7 +303,7 @@ def main() -> int:
                   else f"frames/sec through encode+lookup+exit ({w.name} exits)",
         "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16" if w.dtype == "f16" else "f32", "data": "synthetic",
+        "dtype": "f16" if w.dtype == "f16" else "f32", "accumulate": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}-shaped: batch {B}, {L} exit points "
                                + ",".join(f"[{c},{h},{wd}]" for c, h, wd in w.exits)
                                + f", {n} classes, hot {w.hot}, tau {w.tau}, tiers {w.tiers}, survivors gathered, "
