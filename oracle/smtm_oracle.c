@@ -21,7 +21,7 @@
  *
  * Readings taken where the paper is silent are marked "reading:" below.
  *
- * Parity pins: every function here is pinned by tests/test_oracle_*.py
+ * Parity pins: every function here (orc_cosine_abs_scale included) is pinned by tests/test_oracle_*.py
  * against closed forms, library routines, invariants and brute force.
  */
 #include <math.h>

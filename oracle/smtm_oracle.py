@@ -152,6 +152,13 @@ def cosine(v, c) -> float:
     return float(lib().orc_cosine(_p(v), _p(c), v.shape[0]))
 
 
+def cosine_abs_scale(v, c) -> float:
+    """Rounding-error scale of the cosine: sum |v_k||c_k| / (|v||c|) (the tests' tolerance unit)."""
+    v = _c(v, np.float64); c = _c(c, np.float64)
+    assert v.shape == c.shape and v.ndim == 1
+    return float(lib().orc_cosine_abs_scale(_p(v), _p(c), v.shape[0]))
+
+
 def weight(l: int) -> float:
     return float(lib().orc_weight(l))
 

@@ -36,6 +36,9 @@ MUTANTS = [
     ("Eq. 7 stops one exit point early", "for (int l0 = 1; l0 <= l; ++l0) {", "for (int l0 = 1; l0 < l; ++l0) {"),
     ("in-place forgetting halves", "if (TS[i] % W == 0) FT[i] /= 4;", "if (TS[i] % W == 0) FT[i] /= 2;"),
     ("fp16 exponent bias off by one", "expo - 15);", "expo - 14);"),
+    ("tolerance scale loses its absolute values", "dot += fabs(v[k] * c[k]);", "dot += v[k] * c[k];"),
+    ("tolerance scale ten times too large", "dot += fabs(v[k] * c[k]);\n        vv += v[k] * v[k];",
+     "dot += fabs(v[k] * c[k]);\n        vv += 0.01 * v[k] * v[k];"),
     ("compaction keeps slots instead of frame ids", "live_ids[nl] = frame_ids[i];", "live_ids[nl] = (int32_t)i;"),
 ]
 

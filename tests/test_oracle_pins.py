@@ -132,6 +132,65 @@ def test_cosine_zero_or_nonfinite_vector_gives_zero():
     assert O.cosine(w, v) == 0.0
 
 
+# ------------------------------------------------------------------ tolerance scale of Eq. 1
+
+def test_abs_scale_is_the_sum_of_absolute_products_over_the_norms():
+    # brute force with Python floats, one term at a time
+    for C in (1, 2, 7, 33):
+        for _ in range(6):
+            v = rng.standard_normal(C); c = rng.standard_normal(C)
+            num = 0.0
+            for k in range(C):
+                num += abs(float(v[k])) * abs(float(c[k]))
+            want = num / (math.sqrt(sum(float(x) ** 2 for x in v)) * math.sqrt(sum(float(x) ** 2 for x in c)))
+            assert abs(O.cosine_abs_scale(v, c) - want) <= 1e-15
+
+
+def test_abs_scale_hand_values():
+    # (3,-4).(4,3) = 0 but |3*4| + |-4*3| = 24 over norms 5*5
+    assert abs(O.cosine_abs_scale(np.array([3.0, -4.0]), np.array([4.0, 3.0])) - 24.0 / 25.0) < 1e-15
+    assert O.cosine(np.array([3.0, -4.0]), np.array([4.0, 3.0])) == 0.0
+    # (1,0) against (1,1): 1 / sqrt(2); an orthogonal basis pair has no overlapping terms at all
+    assert abs(O.cosine_abs_scale(np.array([1.0, 0.0]), np.array([1.0, 1.0])) - math.sqrt(0.5)) < 1e-15
+    assert O.cosine_abs_scale(np.array([1.0, 0.0]), np.array([0.0, 1.0])) == 0.0
+
+
+def test_abs_scale_bounds_the_cosine_and_is_at_most_one():
+    for _ in range(50):
+        C = int(rng.integers(1, 40))
+        v = rng.standard_normal(C); c = rng.standard_normal(C)
+        a = O.cosine_abs_scale(v, c)
+        assert abs(O.cosine(v, c)) <= a + 1e-15 and a <= 1.0 + 1e-15      # triangle inequality, Cauchy-Schwarz
+        # invariant to the signs and to positive scaling of either argument, symmetric
+        assert abs(O.cosine_abs_scale(-v, 3.0 * c) - a) < 1e-15
+        assert abs(O.cosine_abs_scale(np.abs(v), c) - a) < 1e-15
+        assert O.cosine_abs_scale(c, v) == a
+
+
+def test_abs_scale_is_one_for_parallel_vectors_and_the_cosine_for_non_negative_ones():
+    v = np.abs(rng.standard_normal(19)) + 0.1
+    assert abs(O.cosine_abs_scale(v, 2.5 * v) - 1.0) <= 4e-16
+    assert abs(O.cosine_abs_scale(v, -v) - 1.0) <= 4e-16                  # the cosine is -1 there, the scale +1
+    c = np.abs(rng.standard_normal(19))
+    assert abs(O.cosine_abs_scale(v, c) - O.cosine(v, c)) <= 1e-15
+
+
+def test_abs_scale_of_a_zero_or_nonfinite_vector_is_zero():
+    z = np.zeros(5); v = np.arange(1.0, 6.0)
+    assert O.cosine_abs_scale(z, v) == 0.0 and O.cosine_abs_scale(v, z) == 0.0
+    w = v.copy(); w[2] = np.inf
+    assert O.cosine_abs_scale(w, v) == 0.0
+
+
+def test_lookup_reports_the_abs_scale_of_every_similarity():
+    # the scale array that the GPU parity tests divide by comes out of orc_lookup
+    SV = rng.standard_normal((4, 9)); SC = rng.standard_normal((6, 9))
+    SA = np.zeros((4, 6))
+    out = O.lookup(SV, SC, 1, np.arange(4, dtype=np.int32), SA, np.array([0, 1], np.int32), 2, 1.0, want_sims=True)
+    want = (np.abs(SV) @ np.abs(SC).T) / (np.linalg.norm(SV, axis=1)[:, None] * np.linalg.norm(SC, axis=1)[None, :])
+    assert np.allclose(out["sims_scale"], want, rtol=0, atol=1e-15)
+
+
 def test_lookup_cached_vector_scores_one_against_itself():
     # a frame whose semantic vector IS centre j scores cosine 1 with j.
     n, C = 12, 64
