@@ -41,3 +41,15 @@ def test_rule_fp32_is_the_exit_rule_in_single_precision():
     assert P.rule_fp32(3.0, 1.0, 1.9) and not P.rule_fp32(3.0, 1.0, 2.0)      # AC = 2: strict >
     assert P.rule_fp32(0.2, -0.1, 100.0)                                     # runner-up not positive
     assert not P.rule_fp32(0.0, -0.1, 0.0) and not P.rule_fp32(-0.1, -0.2, 0.0)
+
+
+def test_narrow_band_is_relative_to_the_frames_own_values():
+    tau, l, d = 4.0, 2, 2e-3
+    h, sh = 0.5, 0.1                                        # on the threshold
+    assert P.in_narrow_band(h, sh, tau, l, d)
+    edge = d * (abs(h) + (1 + tau) * abs(sh))
+    assert P.in_narrow_band(h + 0.9 * edge, sh, tau, l, d) and not P.in_narrow_band(h + 1.2 * edge, sh, tau, l, d)
+    # small accumulated similarities: the narrow band shrinks with them, the propagated one does not
+    assert not P.in_narrow_band(0.012, 0.001, tau, l, d) and P.in_band(0.012, 0.001, tau, l, d, scale=2.0)
+    assert P.in_narrow_band(0.9 * d * 3.0, -0.2, tau, l, d)  # sign of SA_H uncertain
+    assert not P.in_narrow_band(float("nan"), 0.1, tau, l, d)
