@@ -90,6 +90,9 @@ int32_t smtm_destroy(smtm_ctx* ctx);
 const char* smtm_last_error(const smtm_ctx* ctx);
 /* Library version, major*10000 + minor*100 + patch. */
 int32_t smtm_version(void);
+/* Hash (16 hex digits) of the sources the library was built from; the Python binding compares it with
+ * the sources in the tree and rebuilds a stale library. */
+const char* smtm_build_id(void);
 
 /* ---- memory (Sec. 6: global memory, fast memory) ----------------------------------------- */
 
@@ -109,7 +112,14 @@ int32_t smtm_memory_load(smtm_ctx* ctx, int32_t exit, const float* centres_host,
  * been encoded (or has been looked up), SHAPE when batch differs from the batch begun. */
 int32_t smtm_warmup_begin(smtm_ctx* ctx, void* stream);
 int32_t smtm_warmup_batch(smtm_ctx* ctx, const int32_t* label, int32_t batch, void* stream);
-/* Sets the fast memory Psi to k distinct class ids (host), hot_min <= k <= hot_max. */
+/* Restores one exit point's centres AND their update counts m (Eq. 7) from host buffers, as written by
+ * smtm_memory_export: [n, C_l] fp32 and [n] uint32, both required, copied (the buffers must stay valid until
+ * the stream has passed this call).  Together with smtm_tables_import and smtm_hot_set this puts a saved
+ * memory (centres, m, FT, TS, Psi) back so that inference and the memory update continue bit-identically. */
+int32_t smtm_memory_import(smtm_ctx* ctx, int32_t exit, const float* centres_host,
+                           const uint32_t* counts_host, void* stream);
+/* Sets the fast memory Psi to k distinct class ids (host), hot_min <= k <= hot_max.  The ids are copied
+ * before the call returns. */
 int32_t smtm_hot_set(smtm_ctx* ctx, const int32_t* class_ids_host, int32_t k, void* stream);
 /* Copies one exit point's centres ([n, C_l] fp32) and update counts ([n] uint32) to host
  * buffers (either may be NULL).  Synchronises the stream. */
@@ -208,6 +218,11 @@ int32_t smtm_stage_nhwc(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t d
                         int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev,
                         void* fmap_out, void* stream);
 
+/* Name of the kernel instance that the last smtm_encode / smtm_encode_nhwc / smtm_stage of this exit point
+ * launched (for reports; "" before the first encode).  The pointer stays valid until the next encode of
+ * that exit point. */
+const char* smtm_encode_kernel(const smtm_ctx* ctx, int32_t exit);
+
 /* Device pointer to the context's current live list (original frame ids, ascending; the live
  * count is on the device, see smtm_read_counts).  Valid as row_ids for smtm_encode /
  * smtm_exit_compact / smtm_stage of the next exit point; it is overwritten two
@@ -233,7 +248,9 @@ int32_t smtm_read_stats(smtm_ctx* ctx, int32_t* stats_host, void* stream);
 /* Memory update with the batch's outputs, frames taken in original order:
  *   label[b]      device int32 [batch]: recognised class or -1 (nothing recognised)
  *   stop_layer[b] device int32 [batch]: exit point at which inference stopped, 0 = do not
- *                 update centres with this frame
+ *                 update centres with this frame.  Cut down to the exit points the frame has a saved
+ *                 semantic vector for: the exit point at which the library released it, or, for a frame
+ *                 that ran on, the exit points encoded in this batch
  *   Both NULL: the batch's own results are used (what smtm_batch_results would return: label
  *   and exit point of the frames released so far, -1 / 0 for the others).
  * (i)  FT_j += 1 for the frame's class, TS_i = consecutive frames without class i (Sec. 6.1);

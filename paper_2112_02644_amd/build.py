@@ -1,7 +1,9 @@
 """Builds libsmtm.so (the C-ABI library of include/smtm.h) for gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
+import hashlib
 import os
+import re
 import subprocess
 import sys
 from pathlib import Path
@@ -27,8 +29,30 @@ def hipcc() -> str:
     return "hipcc"
 
 
+def _deps():
+    return [CSRC / s for s in SOURCES] + [CSRC / "internal.h", PKG.parent / "include" / "smtm.h"]
+
+
+def source_id() -> str:
+    """Short hash of everything the library is built from (sources, headers, flags)."""
+    h = hashlib.sha256(" ".join(FLAGS).encode())
+    for d in _deps():
+        h.update(d.name.encode())
+        h.update(d.read_bytes())
+    return h.hexdigest()[:16]
+
+
+def built_id():
+    """The source hash compiled into libsmtm.so (read from the file, without loading it), or None."""
+    try:
+        m = re.search(rb"SMTM_BUILD_ID=([0-9a-f]{16})", LIB.read_bytes())
+    except OSError:
+        return None
+    return m.group(1).decode() if m else None
+
+
 def build(verbose: bool = True) -> Path:
-    cmd = [hipcc(), *FLAGS, "-o", str(LIB)] + [str(CSRC / s) for s in SOURCES]
+    cmd = [hipcc(), *FLAGS, f'-DSMTM_BUILD_ID="{source_id()}"', "-o", str(LIB)] + [str(CSRC / s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
@@ -36,11 +60,9 @@ def build(verbose: bool = True) -> Path:
 
 
 def needs_build() -> bool:
-    if not LIB.exists():
-        return True
-    t = LIB.stat().st_mtime
-    deps = [CSRC / s for s in SOURCES] + [CSRC / "internal.h", PKG.parent / "include" / "smtm.h"]
-    return any(d.stat().st_mtime > t for d in deps)
+    """True when there is no library or it was built from other sources than the ones in the tree
+    (compared by content, so copying the tree elsewhere does not matter)."""
+    return built_id() != source_id()
 
 
 if __name__ == "__main__":

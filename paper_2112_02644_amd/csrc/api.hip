@@ -57,14 +57,20 @@ struct smtm_ctx {
     int32_t* below;                              // [1] classes whose prefix share is below the confidence level
     int32_t* order;
     int32_t* all_exits;                          // [max_batch] filled with L: "stopped at the last exit point"
-    // pinned staging for small host -> device copies
+    // pinned staging for small host -> device copies: a ring of slots, each guarded by an event that is
+    // recorded behind the copy that reads it, so that a call only waits when every slot is still in flight
+    static constexpr int kStageSlots = 4;
     void* pinned;
-    size_t pinned_bytes;
+    size_t pinned_bytes;                         // per slot
+    hipEvent_t stage_ev[kStageSlots];
+    bool stage_used[kStageSlots];
+    int stage_next;
 
     // host-side bookkeeping
     int batch;                                   // 0 = no batch begun
     int stage_done[SMTM_MAX_EXITS];              // 0 none, 1 encoded, 2 looked up, 3 compacted
     int enc_dtype[SMTM_MAX_EXITS];
+    char enc_kernel[SMTM_MAX_EXITS][96];         // name of the kernel instance the last encode of each exit point launched
     std::vector<void*> allocs;
 };
 
@@ -149,7 +155,19 @@ static int32_t check_ctx_exit(smtm_ctx* ctx, int32_t exit) {
 
 extern "C" {
 
-int32_t smtm_version(void) { return 100; }
+int32_t smtm_version(void) { return 200; }
+
+#ifndef SMTM_BUILD_ID
+#define SMTM_BUILD_ID "0000000000000000"
+#endif
+// The marker in front of the id lets the build script find it in the file without loading the library.
+static const char kBuildId[] = "SMTM_BUILD_ID=" SMTM_BUILD_ID;
+const char* smtm_build_id(void) { return kBuildId + 14; }
+
+const char* smtm_encode_kernel(const smtm_ctx* ctx, int32_t exit) {
+    if (!ctx || exit < 1 || exit > ctx->cfg.n_exits) return "";
+    return ctx->enc_kernel[exit - 1];
+}
 
 const char* smtm_last_error(const smtm_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
 
@@ -216,7 +234,8 @@ int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
     CREATE_TRY(dev_alloc(ctx, &ctx->below, (size_t)1));
     CREATE_TRY(dev_alloc(ctx, &ctx->all_exits, (size_t)B));
     ctx->pinned_bytes = sizeof(int32_t) * (size_t)cfg->hot_max;
-    CREATE_TRY(hipHostMalloc(&ctx->pinned, ctx->pinned_bytes, hipHostMallocDefault));
+    CREATE_TRY(hipHostMalloc(&ctx->pinned, ctx->pinned_bytes * smtm_ctx::kStageSlots, hipHostMallocDefault));
+    for (int i = 0; i < smtm_ctx::kStageSlots; ++i) CREATE_TRY(hipEventCreateWithFlags(&ctx->stage_ev[i], hipEventDisableTiming));
 
     // initial state on the null stream: zero centres / tables, fast memory = classes 0..hot_init-1
     for (int l = 0; l < L; ++l) {
@@ -257,6 +276,8 @@ int32_t smtm_destroy(smtm_ctx* ctx) {
     (void)hipDeviceSynchronize();
     for (void* p : ctx->allocs) (void)hipFree(p);
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    for (int i = 0; i < smtm_ctx::kStageSlots; ++i)
+        if (ctx->stage_ev[i]) (void)hipEventDestroy(ctx->stage_ev[i]);
     delete ctx;
     return SMTM_OK;
 }
@@ -273,6 +294,19 @@ int32_t smtm_memory_load(smtm_ctx* ctx, int32_t exit, const float* centres_host,
     return check_launch(ctx, "smtm_memory_load");
 }
 
+int32_t smtm_memory_import(smtm_ctx* ctx, int32_t exit, const float* centres_host, const uint32_t* counts_host,
+                           void* stream) {
+    int32_t rc = check_ctx_exit(ctx, exit);
+    if (rc) return rc;
+    if (!centres_host || !counts_host) return fail(ctx, SMTM_ERR_INVALID_ARG, "centres_host / counts_host is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int l = exit - 1, n = ctx->cfg.n_classes, C = ctx->cfg.dims[l];
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->centres[l], centres_host, sizeof(float) * (size_t)n * C, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->mcount[l], counts_host, sizeof(uint32_t) * (size_t)n, hipMemcpyHostToDevice, st));
+    launch_centre_prepare(ctx->centres[l], n, C, ctx->cinv[l], ctx->chat[l], ctx->Cp[l], 0, ctx->n_pad, st);
+    return check_launch(ctx, "smtm_memory_import");
+}
+
 int32_t smtm_hot_set(smtm_ctx* ctx, const int32_t* ids, int32_t k, void* stream) {
     if (int32_t rc = check_ctx(ctx)) return rc;
     if (!ids) return fail(ctx, SMTM_ERR_INVALID_ARG, "class_ids_host is NULL");
@@ -285,10 +319,15 @@ int32_t smtm_hot_set(smtm_ctx* ctx, const int32_t* ids, int32_t k, void* stream)
         seen[ids[i]] = 1;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // the pinned staging buffer may still be in flight from an earlier call on this stream
-    HIP_TRY(ctx, hipStreamSynchronize(st));
-    memcpy(ctx->pinned, ids, sizeof(int32_t) * (size_t)k);
-    HIP_TRY(ctx, hipMemcpyAsync(ctx->ids_stage, ctx->pinned, sizeof(int32_t) * (size_t)k, hipMemcpyHostToDevice, st));
+    // next staging slot; the host waits only if the copy that last read this slot has not run yet
+    const int slot = ctx->stage_next;
+    ctx->stage_next = (slot + 1) % smtm_ctx::kStageSlots;
+    if (ctx->stage_used[slot]) HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev[slot]));
+    void* stage = static_cast<char*>(ctx->pinned) + ctx->pinned_bytes * (size_t)slot;
+    memcpy(stage, ids, sizeof(int32_t) * (size_t)k);
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->ids_stage, stage, sizeof(int32_t) * (size_t)k, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipEventRecord(ctx->stage_ev[slot], st));
+    ctx->stage_used[slot] = true;
     launch_set_hot(ctx->ids_stage, k, ctx->cfg.n_classes, ctx->hot_ids, ctx->in_hot, ctx->counts, st);
     return check_launch(ctx, "smtm_hot_set");
 }
@@ -369,10 +408,10 @@ static int32_t encode_any(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t
     const int l = exit - 1;
     if (channels_last)
         launch_encode_nhwc(fmap, dtype, ctx->cfg.dims[l], H * W, row_ids, ctx->live[ctx->cur], ctx->counts,
-                           ctx->batch, ctx->sv[l], sv_out, st);
+                           ctx->batch, ctx->sv[l], sv_out, st, ctx->enc_kernel[l], sizeof(ctx->enc_kernel[l]));
     else
         launch_encode(fmap, dtype, ctx->cfg.dims[l], H * W, row_ids, ctx->live[ctx->cur], ctx->counts, ctx->batch,
-                      ctx->sv[l], sv_out, st);
+                      ctx->sv[l], sv_out, st, ctx->enc_kernel[l], sizeof(ctx->enc_kernel[l]));
     rc = check_launch(ctx, "smtm_encode");
     if (rc) return rc;
     ctx->stage_done[l] = 1;
@@ -588,6 +627,10 @@ static CentreTables centre_tables(const smtm_ctx* ctx) {
         tabs.C[l] = on ? ctx->cfg.dims[l] : 0;
         tabs.Cp[l] = on ? ctx->Cp[l] : 0;
     }
+    tabs.res_layer = ctx->res_layer;
+    int upto = 0;
+    while (upto < ctx->cfg.n_exits && ctx->stage_done[upto] >= 1) ++upto;
+    tabs.enc_upto = upto;
     return tabs;
 }
 
@@ -621,8 +664,8 @@ int32_t smtm_warmup_batch(smtm_ctx* ctx, const int32_t* label, int32_t batch, vo
     return SMTM_OK;
 }
 
-int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* stop_layer, int32_t batch, void* stream) {
-    if (int32_t rc = check_ctx(ctx)) return rc;
+static int32_t cache_update_with(smtm_ctx* ctx, const int32_t* label, const int32_t* stop_layer, int32_t batch,
+                                 void* stream, const UpdateScratch& us, const char* who) {
     if ((label == nullptr) != (stop_layer == nullptr))
         return fail(ctx, SMTM_ERR_INVALID_ARG, "label and stop_layer must be given together (or both NULL)");
     if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");
@@ -631,12 +674,18 @@ int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* st
     hipStream_t st = static_cast<hipStream_t>(stream);
     const smtm_config& c = ctx->cfg;
     const int n = c.n_classes;
-    launch_tables_update(label, batch, n, (uint32_t)c.window, ctx->FT, ctx->TS, ctx->cls_cnt, ctx->cls_last,
-                         ctx->score, ctx->score_total, ctx->below, c.forgetting, st);
-    launch_centres_and_policy(centre_tables(ctx), c.n_exits, n, label, stop_layer, batch, ctx->cls_cnt, ctx->score,
-                              ctx->score_total, (uint32_t)c.cl_num, (uint32_t)c.cl_den, c.hot_min, c.hot_max,
-                              ctx->order, ctx->below, ctx->hot_ids, ctx->in_hot, ctx->counts, st);
-    return check_launch(ctx, "smtm_cache_update");
+    launch_tables_update(label, batch, n, (uint32_t)c.window, ctx->FT, ctx->TS, us.cls_cnt, us.cls_last,
+                         us.score, us.total, us.below, c.forgetting, st);
+    launch_centres_and_policy(centre_tables(ctx), c.n_exits, n, label, stop_layer, batch, us.cls_cnt, us.score,
+                              us.total, (uint32_t)c.cl_num, (uint32_t)c.cl_den, c.hot_min, c.hot_max,
+                              us.order, us.below, ctx->hot_ids, ctx->in_hot, ctx->counts, st);
+    return check_launch(ctx, who);
+}
+
+int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* stop_layer, int32_t batch, void* stream) {
+    if (int32_t rc = check_ctx(ctx)) return rc;
+    const UpdateScratch us = {ctx->cls_cnt, ctx->cls_last, ctx->score, ctx->order, ctx->score_total, ctx->below};
+    return cache_update_with(ctx, label, stop_layer, batch, stream, us, "smtm_cache_update");
 }
 
 }  // extern "C"

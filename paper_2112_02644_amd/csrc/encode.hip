@@ -13,6 +13,8 @@
 //           consecutive channels (one contiguous piece of the frame) with 16-byte loads into
 //           its own LDS region, then lane c adds up channel c from LDS.
 // Work is taken in a grid-stride loop bounded by the live count read on the device.
+#include <stdio.h>
+
 #include "internal.h"
 
 namespace smtm {
@@ -431,7 +433,7 @@ static int encode_grid(int64_t tasks_upper, int waves_per_block) {
 template <typename T, int VB>
 static void launch_direct(const void* fmap, int C, int HW, const int32_t* row_ids,
                           const int32_t* frame_ids, const Counts* counts, int max_rows, float* sv,
-                          float* sv_out, hipStream_t st) {
+                          float* sv_out, hipStream_t st, char* name, size_t name_cap) {
     constexpr int UNR = 8;
     const int nv = (int)((int64_t)HW * sizeof(T) / VB);
     int g_log2 = 0;
@@ -457,11 +459,13 @@ static void launch_direct(const void* fmap, int C, int HW, const int32_t* row_id
         SMTM_LAUNCH_DIRECT(-1);
     }
 #undef SMTM_LAUNCH_DIRECT
+    if (name) snprintf(name, name_cap, "k_encode_direct<%s,%dB,%d lanes per channel>", sizeof(T) == 2 ? "f16" : "f32", VB, 1 << g_log2);
 }
 
 template <typename T>
 static void launch_pair(const void* fmap, int C, int HW, const int32_t* row_ids, const int32_t* frame_ids,
-                        const Counts* counts, int max_rows, float* sv, float* sv_out, hipStream_t st) {
+                        const Counts* counts, int max_rows, float* sv, float* sv_out, hipStream_t st, char* name,
+                        size_t name_cap) {
     constexpr int UNR = 8;
     const int nv2 = (int)((int64_t)HW * sizeof(T) / 8);
     int g_log2 = 0;
@@ -471,27 +475,28 @@ static void launch_pair(const void* fmap, int C, int HW, const int32_t* row_ids,
     const int grid = encode_grid(tasks, 4);
     hipLaunchKernelGGL((k_encode_pair<T, UNR>), dim3(grid), dim3(256), 0, st, static_cast<const T*>(fmap),
                        row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW, g_log2);
+    if (name) snprintf(name, name_cap, "k_encode_pair<%s,%d lanes per pair>", sizeof(T) == 2 ? "f16" : "f32", 1 << g_log2);
 }
 
 const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
                           const int32_t* frame_ids, const Counts* counts, int max_rows,
-                          float* sv, float* sv_out, hipStream_t st) {
+                          float* sv, float* sv_out, hipStream_t st, char* name, size_t name_cap) {
     const int esz = dtype == SMTM_F16 ? 2 : 4;
     const int64_t ch_bytes = (int64_t)HW * esz;
     const int64_t frame_bytes = ch_bytes * C;
     if (ch_bytes % 16 == 0) {
-        if (dtype == SMTM_F16) launch_direct<_Float16, 16>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
-        else launch_direct<float, 16>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        if (dtype == SMTM_F16) launch_direct<_Float16, 16>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st, name, name_cap);
+        else launch_direct<float, 16>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st, name, name_cap);
         return "d16";
     }
     if (ch_bytes % 8 == 0 && (C & 1) == 0) {
-        if (dtype == SMTM_F16) launch_pair<_Float16>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
-        else launch_pair<float>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        if (dtype == SMTM_F16) launch_pair<_Float16>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st, name, name_cap);
+        else launch_pair<float>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st, name, name_cap);
         return "pair";
     }
     if (ch_bytes % 8 == 0) {
-        if (dtype == SMTM_F16) launch_direct<_Float16, 8>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
-        else launch_direct<float, 8>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        if (dtype == SMTM_F16) launch_direct<_Float16, 8>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st, name, name_cap);
+        else launch_direct<float, 8>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st, name, name_cap);
         return "d8";
     }
     if (frame_bytes % 16 == 0 && ch_bytes <= 256) {
@@ -512,20 +517,21 @@ const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int3
         if (dtype == SMTM_F16) { if (ch_bytes <= 128) SMTM_LAUNCH_LDS(_Float16, 8); else SMTM_LAUNCH_LDS(_Float16, 16); }
         else                   { if (ch_bytes <= 128) SMTM_LAUNCH_LDS(float, 8);    else SMTM_LAUNCH_LDS(float, 16); }
 #undef SMTM_LAUNCH_LDS
+        if (name) snprintf(name, name_cap, "k_encode_lds<%s,%d loads per lane>", dtype == SMTM_F16 ? "f16" : "f32", ch_bytes <= 128 ? 8 : 16);
         return "lds";
     }
     if (ch_bytes % 4 == 0) {
-        if (dtype == SMTM_F16) launch_direct<_Float16, 4>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
-        else launch_direct<float, 4>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+        if (dtype == SMTM_F16) launch_direct<_Float16, 4>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st, name, name_cap);
+        else launch_direct<float, 4>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st, name, name_cap);
         return "d4";
     }
-    launch_direct<_Float16, 2>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st);
+    launch_direct<_Float16, 2>(fmap, C, HW, row_ids, frame_ids, counts, max_rows, sv, sv_out, st, name, name_cap);
     return "d2";
 }
 
 const char* launch_encode_nhwc(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
                                const int32_t* frame_ids, const Counts* counts, int max_rows,
-                               float* sv, float* sv_out, hipStream_t st) {
+                               float* sv, float* sv_out, hipStream_t st, char* name, size_t name_cap) {
     const int E = dtype == SMTM_F16 ? 8 : 4;
     if (C % E == 0) {
         const int cpr = C / E;
@@ -543,6 +549,7 @@ const char* launch_encode_nhwc(const void* fmap, int dtype, int C, int HW, const
         else
             hipLaunchKernelGGL((k_encode_nhwc<float, 8>), dim3(grid), dim3(nw * 64), lds, st,
                                static_cast<const float*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW);
+        if (name) snprintf(name, name_cap, "k_encode_nhwc<%s,%d wavefronts>", dtype == SMTM_F16 ? "f16" : "f32", nw);
         return "nhwc16";
     }
     const int grid = encode_grid((int64_t)max_rows * ((C + 255) / 256), 1);
@@ -552,6 +559,7 @@ const char* launch_encode_nhwc(const void* fmap, int dtype, int C, int HW, const
     else
         hipLaunchKernelGGL((k_encode_nhwc_scalar<float>), dim3(grid), dim3(256), 0, st,
                            static_cast<const float*>(fmap), row_ids, frame_ids, counts, max_rows, sv, sv_out, C, HW);
+    if (name) snprintf(name, name_cap, "k_encode_nhwc_scalar<%s>", dtype == SMTM_F16 ? "f16" : "f32");
     return "nhwc1";
 }
 

@@ -39,15 +39,16 @@ constexpr int kRowPad = 128;              // fp16 operand matrices are padded to
 static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // ---- encode.hip -------------------------------------------------------------------------
-// Picks the streaming path from the shape; returns a short name of the path ("d16", "pair", "d8", "lds", "d4", "d2").
+// Picks the streaming path from the shape; returns a short name of the path ("d16", "pair", "d8", "lds", "d4", "d2")
+// and writes the name of the kernel instance it launched to `name`.
 const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
                           const int32_t* frame_ids, const Counts* counts, int max_rows,
-                          float* sv_by_frame, float* sv_out_by_slot, hipStream_t st);
+                          float* sv_by_frame, float* sv_out_by_slot, hipStream_t st, char* name, size_t name_cap);
 
 // Channels-last variant: fmap is [rows, H, W, C].
 const char* launch_encode_nhwc(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
                                const int32_t* frame_ids, const Counts* counts, int max_rows,
-                               float* sv_by_frame, float* sv_out_by_slot, hipStream_t st);
+                               float* sv_by_frame, float* sv_out_by_slot, hipStream_t st, char* name, size_t name_cap);
 
 // ---- lookup.hip -------------------------------------------------------------------------
 void launch_centre_prepare(const float* centres, int n, int C, float* cinv, _Float16* chat, int Cp,
@@ -90,7 +91,20 @@ struct CentreTables {                     // per exit point, passed by value to 
     const float* sv[SMTM_MAX_EXITS];
     int C[SMTM_MAX_EXITS];
     int Cp[SMTM_MAX_EXITS];
+    const int32_t* res_layer;             // [batch] exit point at which the library released the frame, 0 = not released
+    int enc_upto;                         // exit points 1..enc_upto have been encoded in this batch
 };
+// The scratch arrays of one memory update (class histogram, last positions, scores, policy order, the
+// 128-bit score total and the policy counter).
+struct UpdateScratch {
+    uint32_t* cls_cnt;
+    int32_t* cls_last;
+    uint64_t* score;
+    int32_t* order;
+    uint64_t* total;
+    int32_t* below;
+};
+
 void launch_tables_update(const int32_t* label, int batch, int n, uint32_t W, uint32_t* FT, uint32_t* TS,
                           uint32_t* cls_cnt, int32_t* cls_last, uint64_t* score, uint64_t* total,
                           int32_t* below, int inplace, hipStream_t st);

@@ -155,9 +155,19 @@ void launch_class_count(const int32_t* label, int batch, int n, uint32_t* cls_cn
 // fp16 copy of the row.
 constexpr int kListCap = 4096;
 
+// A frame's saved semantic vectors exist only for the exit points it was live at: one that the library
+// released at exit point r has them for 1..r, one that ran on has them for the exit points encoded in
+// this batch (1..enc_upto).  A larger stop_layer is cut down to that.
+__device__ __forceinline__ int usable_stop(int stop, int released_at, int enc_upto) {
+    const int have = released_at > 0 ? released_at : enc_upto;
+    return stop < have ? stop : have;
+}
+
 __device__ __forceinline__ void centres_block(const CentreTables& tabs, const int32_t* __restrict__ label,
                                               const int32_t* __restrict__ stop_layer, int batch,
                                               const uint32_t* __restrict__ cls_cnt, int j, int l0) {
+    const int32_t* __restrict__ res_layer = tabs.res_layer;
+    const int enc_upto = tabs.enc_upto;
     __shared__ int list[kListCap];
     __shared__ int w_cnt[4];
     __shared__ float red[4];
@@ -173,19 +183,21 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
     // pass; its hits go behind those of the lower lanes and wavefronts, which keeps the list in frame order.
     int cnt = 0;
     bool overflow = false;
-    const bool vec_ok = ((reinterpret_cast<uintptr_t>(label) | reinterpret_cast<uintptr_t>(stop_layer)) & 15u) == 0;
+    const bool vec_ok = ((reinterpret_cast<uintptr_t>(label) | reinterpret_cast<uintptr_t>(stop_layer) |
+                          reinterpret_cast<uintptr_t>(res_layer)) & 15u) == 0;
     for (int b0 = 0; b0 < batch; b0 += 1024) {           // uniform trip count
         const int b = b0 + 4 * tid;
         int lab[4] = {-1, -1, -1, -1}, stp[4] = {0, 0, 0, 0};
         if (vec_ok && b + 3 < batch) {
             const i32x4 lv = *reinterpret_cast<const i32x4*>(label + b);
             const i32x4 sv4 = *reinterpret_cast<const i32x4*>(stop_layer + b);
+            const i32x4 rl4 = *reinterpret_cast<const i32x4*>(res_layer + b);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) { lab[k] = lv[k]; stp[k] = sv4[k]; }
+            for (int k = 0; k < 4; ++k) { lab[k] = lv[k]; stp[k] = usable_stop(sv4[k], rl4[k], enc_upto); }
         } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                if (b + k < batch) { lab[k] = label[b + k]; stp[k] = stop_layer[b + k]; }
+                if (b + k < batch) { lab[k] = label[b + k]; stp[k] = usable_stop(stop_layer[b + k], res_layer[b + k], enc_upto); }
         }
         bool hit[4];
         int pre = 0, tot_w = 0, own = 0;
@@ -286,7 +298,7 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
                 }
             } else {                                     // more frames of one class than the list holds
                 for (int b = 0; b < batch; ++b)
-                    if (label[b] == j && stop_layer[b] > l0) sum += sv[(int64_t)b * C + c];
+                    if (label[b] == j && usable_stop(stop_layer[b], res_layer[b], enc_upto) > l0) sum += sv[(int64_t)b * C + c];
             }
             const float x = (sc[c] * m_old + sum) / (m_old + (float)cnt);
             sc[c] = x;

@@ -73,13 +73,16 @@ class SmtmConfig:
 
 def load_library():
     """Loads libsmtm.so built in-tree (python -m paper_2112_02644_amd.build, or
-    __graft_entry__.build()); builds it once if it has never been built."""
+    __graft_entry__.build()).  A library that is missing, or that was built from other sources than
+    the ones in the tree (their hash is compiled into it), is built first."""
     global _lib
     if _lib is not None:
         return _lib
-    if not _LIB_PATH.exists():
-        from . import build as _b
+    from . import build as _b
+    if _b.needs_build():
         _b.build(verbose=False)
+        if _b.needs_build():
+            raise RuntimeError("libsmtm.so does not match the sources after a rebuild")
     L = C.CDLL(str(_LIB_PATH))
     vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
     sig = {
@@ -107,6 +110,7 @@ def load_library():
         "smtm_read_counts": [vp, vp, vp, vp],
         "smtm_read_stats": [vp, vp, vp],
         "smtm_cache_update": [vp, vp, vp, i32, vp],
+        "smtm_memory_import": [vp, i32, vp, vp, vp],
     }
     for name, args in sig.items():
         fn = getattr(L, name)
@@ -116,6 +120,10 @@ def load_library():
     L.smtm_last_error.restype = C.c_char_p
     L.smtm_live_ids.argtypes = [vp]
     L.smtm_live_ids.restype = vp
+    L.smtm_build_id.argtypes = []
+    L.smtm_build_id.restype = C.c_char_p
+    L.smtm_encode_kernel.argtypes = [vp, i32]
+    L.smtm_encode_kernel.restype = C.c_char_p
     _lib = L
     return L
 
@@ -156,6 +164,7 @@ class Smtm:
         if rc != 0:
             raise SmtmError(rc, self.lib.smtm_last_error(None).decode())
         self.stream = stream
+        self._keep = {}
 
     # -- plumbing
     def _st(self, stream=None):
@@ -189,6 +198,14 @@ class Smtm:
 
     def warmup_batch(self, label, batch: int, stream=None):
         self._ck(self.lib.smtm_warmup_batch(self._h, _ptr(label), batch, self._st(stream)))
+
+    def memory_import(self, exit: int, centres_host, counts_host, stream=None):
+        import numpy as np
+        centres = np.ascontiguousarray(centres_host, dtype=np.float32)
+        counts = np.ascontiguousarray(counts_host, dtype=np.uint32)
+        assert centres.shape == (self.cfg.n_classes, self.cfg.dims[exit - 1]) and counts.shape == (self.cfg.n_classes,)
+        self._ck(self.lib.smtm_memory_import(self._h, exit, _ptr(centres), _ptr(counts), self._st(stream)))
+        self._keep[exit] = (centres, counts)             # the copies are stream-ordered: keep the host arrays alive
 
     def hot_set(self, class_ids_host, stream=None):
         import numpy as np
@@ -278,6 +295,10 @@ class Smtm:
         self._ck(self.lib.smtm_stage_nhwc(self._h, exit, _ptr(fmap), dtype, H, W, _ptr(row_ids), _ptr(exit_ids),
                                           _ptr(exit_labels), _ptr(exit_tier), _ptr(n_exit_dev), _ptr(live_ids),
                                           _ptr(n_live_dev), _ptr(fmap_out), self._st(stream)))
+
+    def encode_kernel(self, exit: int) -> str:
+        """Name of the kernel instance that the last encode of this exit point launched."""
+        return (self.lib.smtm_encode_kernel(self._h, exit) or b"").decode()
 
     def live_ids(self) -> int:
         """Device address of the context's current live list (int32)."""

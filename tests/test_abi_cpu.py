@@ -34,7 +34,7 @@ def test_library_loads_and_exports_every_declared_symbol():
 
 def test_binding_covers_every_declared_symbol():
     methods = {m for m in dir(smtm.Smtm)}
-    skip = {"smtm_create", "smtm_destroy", "smtm_last_error", "smtm_version"}
+    skip = {"smtm_create", "smtm_destroy", "smtm_last_error", "smtm_version", "smtm_build_id"}
     for name in declared_functions():
         if name in skip:
             continue

@@ -934,6 +934,84 @@ def test_cache_update_with_the_batchs_own_results():
         assert np.array_equal(a, b)
 
 
+# ------------------------------------------------------------------ saved state put back (centres, m, FT, TS, fast memory)
+
+def test_exported_state_imported_into_a_new_context_continues_bit_identically():
+    w = dataclasses.replace(configs.ADAPTIVE, batch=256, exits=((64, 14, 14), (96, 7, 7), (128, 4, 4)), n_classes=200,
+                            hot=16, hot_min=8, hot_max=128, window=256, total_frames=256 * 5, drift_every=512, drift_top=10)
+    cents = streams.centroids(w); ls = streams.labels(w)
+    i32 = dict(dtype=torch.int32, device=DEV)
+
+    def run_batch(ctx, b):
+        fm = streams.batch_feature_maps(w, cents, ls, b, DEV)
+        ctx.begin_batch(w.batch)
+        keep = []
+        for l in range(1, w.n_exits + 1):
+            lists = [torch.full((w.batch,), -7, **i32) for _ in range(4)] + [torch.zeros(1, **i32), torch.zeros(1, **i32)]
+            ctx.stage(l, fm[l - 1], row_ids=ctx.live_ids(), exit_ids=lists[0], exit_labels=lists[1], exit_tier=lists[2],
+                      live_ids=lists[3], n_exit_dev=lists[4], n_live_dev=lists[5])
+            keep += lists
+        ctx.cache_update(None, None, w.batch)
+        torch.cuda.synchronize()
+        return [k.cpu().numpy() for k in keep]
+
+    def state(ctx):
+        ft, ts, hot, k = ctx.tables_export()
+        return [ft, ts, hot, np.array([k])] + [x for l in range(1, w.n_exits + 1) for x in ctx.memory_export(l)]
+
+    a = P.make_ctx(w, cents, ls.initial_hot)
+    for b in range(3):
+        run_batch(a, b)
+    saved = state(a)
+    assert saved[0].sum() > 0 and any((m != w.init_count).any() for m in saved[5::2])   # the memory has moved
+    # a new context starts from the initial centres; only the import gives it a's memory
+    zero = [torch.zeros_like(c) for c in cents]
+    b_ctx = P.make_ctx(w, zero, np.arange(w.hot, dtype=np.int32))
+    b_ctx.tables_import(saved[0], saved[1])
+    b_ctx.hot_set(saved[2])
+    for l in range(1, w.n_exits + 1):
+        b_ctx.memory_import(l, saved[4 + 2 * (l - 1)], saved[5 + 2 * (l - 1)])
+    torch.cuda.synchronize()
+    for x, y in zip(saved, state(b_ctx)):
+        assert np.array_equal(x.view(np.int32) if x.dtype == np.float32 else x, y.view(np.int32) if y.dtype == np.float32 else y)
+    for b in (3, 4):
+        out_a, out_b = run_batch(a, b), run_batch(b_ctx, b)
+        for x, y in zip(out_a, out_b):
+            assert np.array_equal(x, y), f"batch {b}: lists differ after the import"
+        for x, y in zip(state(a), state(b_ctx)):
+            assert np.array_equal(x.view(np.int32) if x.dtype == np.float32 else x,
+                                  y.view(np.int32) if y.dtype == np.float32 else y), f"batch {b}: memory differs after the import"
+    assert b_ctx.lib.smtm_memory_import(b_ctx._h, 1, None, None, None) == 1      # both buffers are required
+    a.close(); b_ctx.close()
+
+
+def test_stop_layer_beyond_the_exit_point_of_release_is_cut_down():
+    # a frame released at exit point 1 has no semantic vector at exit points 2..L: stop_layer = L for it
+    # must move the same centres as stop_layer = 1
+    w = dataclasses.replace(configs.RESNET18, batch=128, n_classes=30, hot=30, off_memory=0.0, sigma=0.3)
+    cents = streams.centroids(w); ls = streams.labels(w)
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    outs = []
+    for beyond in (False, True):
+        ctx = P.make_ctx(w, cents, np.arange(30, dtype=np.int32), tau=1.0)
+        for rep in range(2):                               # the second batch would read rows saved by the first
+            ctx.begin_batch(w.batch)
+            for l in range(1, w.n_exits + 1):
+                ctx.stage(l, fm[l - 1], row_ids=ctx.live_ids())
+            res = [torch.zeros(w.batch, dtype=torch.int32, device=DEV) for _ in range(3)]
+            ctx.batch_results(*res)
+            layer = res[0].cpu().numpy()
+            assert (layer == 1).any()
+            label = np.where(layer > 0, res[1].cpu().numpy(), ls.label[: w.batch]).astype(np.int32)
+            stop = np.where(layer > 0, w.n_exits if beyond else layer, w.n_exits).astype(np.int32)
+            ctx.cache_update(torch.from_numpy(label).to(DEV), torch.from_numpy(stop).to(DEV), w.batch)
+        torch.cuda.synchronize()
+        outs.append([ctx.memory_export(l) for l in range(1, w.n_exits + 1)])
+        ctx.close()
+    for (c1, m1), (c2, m2) in zip(*outs):
+        assert np.array_equal(m1, m2) and np.array_equal(c1.view(np.int32), c2.view(np.int32))
+
+
 # ------------------------------------------------------------------ large class counts, large batches, degenerate streams
 
 def test_many_classes_and_long_batch():
