@@ -265,6 +265,18 @@ int32_t smtm_read_stats(smtm_ctx* ctx, int32_t* stats_host, void* stream);
 int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* stop_layer,
                           int32_t batch, void* stream);
 
+/* smtm_cache_update for callers that cannot allocate device memory or tolerate a library that does
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments,
+ * same results, but the update's scratch (class histogram, last positions, scores, policy order, score
+ * total, policy counter; 20 bytes per class) lives in an 82 KB array that is part of the library's
+ * device image instead of in buffers allocated with the context.  The call itself allocates and frees nothing.
+ *   - At most 4096 classes; a context with more gets SMTM_ERR_UNSUPPORTED and nothing is enqueued.
+ *   - Every context on one GPU shares that GPU's array (each GPU has its own copy, held until the process
+ *     ends).  Calls whose kernels may overlap on one GPU (two streams) race on it: order them.
+ *   - Nothing is assumed about what an earlier call left in the array. */
+int32_t smtm_cache_update_static(smtm_ctx* ctx, const int32_t* label, const int32_t* stop_layer,
+                                 int32_t batch, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

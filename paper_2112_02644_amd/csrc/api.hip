@@ -688,4 +688,16 @@ int32_t smtm_cache_update(smtm_ctx* ctx, const int32_t* label, const int32_t* st
     return cache_update_with(ctx, label, stop_layer, batch, stream, us, "smtm_cache_update");
 }
 
+int32_t smtm_cache_update_static(smtm_ctx* ctx, const int32_t* label, const int32_t* stop_layer, int32_t batch,
+                                 void* stream) {
+    if (int32_t rc = check_ctx(ctx)) return rc;
+    if (ctx->cfg.n_classes > kStaticMaxClasses)
+        return fail(ctx, SMTM_ERR_UNSUPPORTED, "smtm_cache_update_static holds scratch for at most %d classes, the context has %d",
+                    kStaticMaxClasses, ctx->cfg.n_classes);
+    UpdateScratch us;
+    const hipError_t e = update_static_scratch(ctx->device, &us);
+    if (e != hipSuccess) return fail(ctx, SMTM_ERR_HIP, "address of the static scratch: %s", hipGetErrorString(e));
+    return cache_update_with(ctx, label, stop_layer, batch, stream, us, "smtm_cache_update_static");
+}
+
 }  // extern "C"

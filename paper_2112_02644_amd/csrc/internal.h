@@ -104,6 +104,9 @@ struct UpdateScratch {
     uint64_t* total;
     int32_t* below;
 };
+constexpr int kStaticMaxClasses = 4096;   // most classes the statically allocated update scratch is laid out for
+// Device addresses of the statically allocated scratch on GPU `device`, which must be the current device.
+hipError_t update_static_scratch(int device, UpdateScratch* out);
 
 void launch_tables_update(const int32_t* label, int batch, int n, uint32_t W, uint32_t* FT, uint32_t* TS,
                           uint32_t* cls_cnt, int32_t* cls_last, uint64_t* score, uint64_t* total,

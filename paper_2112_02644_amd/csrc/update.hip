@@ -3,6 +3,8 @@
 // (Eq. 7).  Tables, scores, order and size are exact integer work; only the centres are
 // floating point.  All of it is a few thousand entries: latency-bound, so the work is spread
 // over many short lanes rather than a few long loops.
+#include <mutex>
+
 #include "internal.h"
 
 namespace smtm {
@@ -436,6 +438,50 @@ void launch_centres_and_policy(const CentreTables& tabs, int n_exits, int n, con
                        batch, cls_cnt, score, total, cl_num, cl_den, order, below);
     hipLaunchKernelGGL(k_policy_finish, dim3(1), dim3(1024), 0, st, total, n, hot_min, hot_max, order, below,
                        hot_ids, in_hot, counts);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scratch of the memory update for callers that cannot allocate: one file-scope device array per
+// GPU, laid out for up to kStaticMaxClasses classes.  The array's name is only a host-side handle;
+// its device address is looked up once per GPU and that address is what kernels are given.
+constexpr size_t kStaticAlign = 256;
+constexpr size_t static_round(size_t x) { return (x + kStaticAlign - 1) / kStaticAlign * kStaticAlign; }
+constexpr size_t kStaticOffCnt = 0;                                                        // uint32 [n]
+constexpr size_t kStaticOffLast = kStaticOffCnt + static_round(4 * (size_t)kStaticMaxClasses);   // int32 [n]
+constexpr size_t kStaticOffScore = kStaticOffLast + static_round(4 * (size_t)kStaticMaxClasses); // uint64 [n]
+constexpr size_t kStaticOffOrder = kStaticOffScore + static_round(8 * (size_t)kStaticMaxClasses);// int32 [n]
+constexpr size_t kStaticOffTotal = kStaticOffOrder + static_round(4 * (size_t)kStaticMaxClasses);// uint64 [2]
+constexpr size_t kStaticOffBelow = kStaticOffTotal + kStaticAlign;                               // int32 [1]
+constexpr size_t kStaticBytes = kStaticOffBelow + kStaticAlign;
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static unsigned char* g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU, once known
+
+hipError_t update_static_scratch(int device, UpdateScratch* out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    unsigned char* base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[device]) {
+            // the caller has made `device` current: the symbol is resolved for that GPU's copy of the array
+            void* p = nullptr;
+            const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (!p) return hipErrorInvalidSymbol;
+            g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+        }
+        base = g_scratch_ptr[device];
+    }
+    out->cls_cnt = reinterpret_cast<uint32_t*>(base + kStaticOffCnt);
+    out->cls_last = reinterpret_cast<int32_t*>(base + kStaticOffLast);
+    out->score = reinterpret_cast<uint64_t*>(base + kStaticOffScore);
+    out->order = reinterpret_cast<int32_t*>(base + kStaticOffOrder);
+    out->total = reinterpret_cast<uint64_t*>(base + kStaticOffTotal);
+    out->below = reinterpret_cast<int32_t*>(base + kStaticOffBelow);
+    return hipSuccess;
 }
 
 }  // namespace smtm

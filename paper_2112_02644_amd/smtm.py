@@ -110,6 +110,7 @@ def load_library():
         "smtm_read_counts": [vp, vp, vp, vp],
         "smtm_read_stats": [vp, vp, vp],
         "smtm_cache_update": [vp, vp, vp, i32, vp],
+        "smtm_cache_update_static": [vp, vp, vp, i32, vp],
         "smtm_memory_import": [vp, i32, vp, vp, vp],
     }
     for name, args in sig.items():
@@ -321,3 +322,6 @@ class Smtm:
     # -- between batches
     def cache_update(self, label, stop_layer, batch: int, stream=None):
         self._ck(self.lib.smtm_cache_update(self._h, _ptr(label), _ptr(stop_layer), batch, self._st(stream)))
+
+    def cache_update_static(self, label, stop_layer, batch: int, stream=None):
+        self._ck(self.lib.smtm_cache_update_static(self._h, _ptr(label), _ptr(stop_layer), batch, self._st(stream)))
