@@ -4,8 +4,10 @@
 A step is one batch of the ResNet-50-shaped workload through every part of the path:
 begin_batch, then at each of the four exit points encode -> lookup -> exit/compact (lists of the
 released frames with labels and tiers, the survivors' feature maps gathered for the next block),
-then the memory update.  Inputs (all four feature-map tensors, 3.08 GB) are resident in HBM before the clock
-starts; nothing is read back inside the timed region.
+then the memory update.  The steps walk along the workload's frame stream: step s processes batch s
+of the stream (up to --distinct batches are generated, 3.08 GB of feature maps each, after which the
+stream wraps around), so the memory update meets new frames at every step.  All inputs are resident in
+HBM before the clock starts; nothing is read back inside the timed region.
 
 Prints one JSON line.  `value` is frames/s over the timed steps.  `roofline` is for the dominant
 kernel (the instance of the 16-byte streaming encode kernel that serves exit point 1), timed with
@@ -52,6 +54,8 @@ def main() -> int:
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--cpu-sample", type=int, default=1024, help="frames of the batch given to the CPU oracle")
     ap.add_argument("--cpu-reps", type=int, default=4, help="times the CPU oracle runs that sample")
+    ap.add_argument("--distinct", type=int, default=24,
+                    help="distinct batches of the stream kept in HBM (the steps wrap around after that many)")
     ap.add_argument("--skip-extras", action="store_true",
                     help="leave out the informational runs after the timed region (no_exit, two_contexts), "
                          "e.g. under a profiler, where their kernels would mix into the per-kernel figures")
@@ -69,9 +73,14 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     B, L, n = w.batch, w.n_exits, w.n_classes
+    from oracle import smtm_oracle as O                     # only the cpu_baseline leg below uses it
+    assert not os.environ.get("SMTM_ORACLE_LIB"), "the CPU baseline is the oracle built from oracle/smtm_oracle.c"
     cents = streams.centroids(w)
-    ls = streams.labels(w, B)
-    fmaps = streams.batch_feature_maps(w, cents, ls, 0, dev)
+    total = args.steps + args.warmup
+    n_distinct = max(1, min(total, args.distinct))
+    ls = streams.labels(w, B * n_distinct)
+    stream_fmaps = [streams.batch_feature_maps(w, cents, ls, b, dev) for b in range(n_distinct)]
+    fmaps = stream_fmaps[0]
     gathers = [torch.empty_like(f) for f in fmaps]
     hot_max = w.hot_max or w.hot
     cfg = SmtmConfig(n_classes=n, dims=w.dims, max_batch=B, hot_init=w.hot,
@@ -87,27 +96,25 @@ def main() -> int:
     exit_ids = [torch.zeros(B, **i32) for _ in range(L)]
     exit_labels = [torch.zeros(B, **i32) for _ in range(L)]
     exit_tier = [torch.zeros(B, **i32) for _ in range(L)]
-    total = args.steps + args.warmup
     live_log = torch.zeros((total, L), **i32)              # survivors after each exit point, per step
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
           for _ in range(total)]
     esz = w.esz
     live_ptr0 = live_log.data_ptr()
-    # dominant kernel: the instance of the 16-byte-load encode kernel that serves the largest feature map
-    # (instances differ in the lanes per channel, 2^g, chosen from the channel's length as the library does)
-    def lanes_log2(h, wd):
-        nv, g = h * wd * esz // 16, 0
-        while g < 6 and (nv + (1 << g) - 1) // (1 << g) > 8:
-            g += 1
-        return g
+    # dominant kernel: the encode kernel instance that serves the largest feature map; the library names the
+    # instance each encode launched, and every exit point served by that same instance is timed with it
     big = max(range(L), key=lambda l: w.exits[l][0] * w.exits[l][1] * w.exits[l][2])
-    dom_g = lanes_log2(w.exits[big][1], w.exits[big][2])
-    dom = [l for l, (c, h, wd) in enumerate(w.exits) if (h * wd * esz) % 16 == 0 and lanes_log2(h, wd) == dom_g]
+    ctx.begin_batch(B)
+    for l in range(1, L + 1):
+        ctx.encode(l, fmaps[l - 1], row_ids=ctx.live_ids())
+    torch.cuda.synchronize()
+    enc_names = [ctx.encode_kernel(l) for l in range(1, L + 1)]
+    dom = [l for l in range(L) if enc_names[l] == enc_names[big]]
 
     def step(s: int):
         ctx.begin_batch(B)
         for l in range(1, L + 1):
-            F = fmaps[l - 1]
+            F = stream_fmaps[s % n_distinct][l - 1]
             ids = ctx.live_ids()
             if (l - 1) in dom:                              # events only around the dominant kernel's launches
                 a, b = ev[s][l - 1]
@@ -270,7 +277,6 @@ def main() -> int:
         except Exception as e:                               # reported, never fatal for the main figure
             print(f"bench.py: single-frame graph run skipped: {e}", file=sys.stderr)
 
-    from oracle import smtm_oracle as O
     ns = min(args.cpu_sample, B)
     host = [f[:ns].cpu().numpy() for f in fmaps]
     cores = O.get_max_threads()
@@ -307,10 +313,10 @@ def main() -> int:
         "config": {"workload": f"{w.name}-shaped: batch {B}, {L} exit points "
                                + ",".join(f"[{c},{h},{wd}]" for c, h, wd in w.exits)
                                + f", {n} classes, hot {w.hot}, tau {w.tau}, tiers {w.tiers}, survivors gathered, "
-                                 "memory update every batch",
+                                 f"memory update every batch, {n_distinct} distinct batches of the stream",
                    "exits_per_exit_point": exits.mean(axis=0).round(1).tolist(),
                    "ran_to_end": float(live[:, -1].mean())},
-        "roofline": {"bound": "hbm", "kernel": f"k_encode_direct<{w.dtype},16B,{1 << dom_g} lanes per channel>", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": enc_names[big], "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "cpu_baseline": {"value": ns * args.cpu_reps / cpu_s, "unit": "frames/s", "cores": cores, "kind": "oracle",
@@ -338,6 +344,7 @@ def main() -> int:
         # survivors after each exit point for every step run (warm-up included), so that per-dispatch
         # byte counts of a profile of this command can be reconstructed
         "survivors_log": live_log.cpu().numpy().tolist(),
+        "encode_kernels": enc_names,
     }
     print(json.dumps(out))
     ctx.close()

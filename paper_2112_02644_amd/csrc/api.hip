@@ -17,10 +17,9 @@ struct smtm_ctx {
     int device;
     char err[512];
 
-    int n_pad;                                   // classes rounded up to kRowPad (fp16 operand rows)
-    int rows_pad;                                // max_batch rounded up to kRowPad
+    int n_pad;                                   // classes rounded up to kRowPad (fp16 operand rows, fast-memory mask)
     int Cp[SMTM_MAX_EXITS];                      // channels rounded up to kKPad
-    int Cp_max;
+    int tiles;                                   // class tiles of the scoring kernels
 
     // global memory (Sec. 6): centres per exit point, update counts, tables
     float* centres[SMTM_MAX_EXITS];              // [n, C_l] fp32 master
@@ -34,10 +33,12 @@ struct smtm_ctx {
     uint8_t* in_hot;                             // [n]
     int32_t* ids_stage;                          // [hot_max] staging for smtm_hot_set
     // batch state
-    float* SA;                                   // [max_batch, n] by original frame id
-    float* sv[SMTM_MAX_EXITS];                   // [max_batch, C_l] by original frame id
-    float* vinv;                                 // [max_batch] by slot
-    _Float16* vhat;                              // [rows_pad, Cp_max] by slot
+    float* SA;                                   // [max_batch, n] by original frame id (+ slack for unguarded tile loads)
+    float* sv[SMTM_MAX_EXITS];                   // [max_batch, Cp_l] by original frame id, columns >= C_l stay zero
+    uint32_t* rowmax;                            // [L, max_batch, kRowMaxSlots] partial maxima of |SV| per frame and exit point
+    int enc_slots[SMTM_MAX_EXITS];               // slots per frame the last encode of each exit point filled
+    float* part;                                 // [tiles, 6, max_batch] per-tile best / second best of the last lookup
+    bool sa_fresh;                               // no lookup yet in this batch: the next one overwrites SA
     int32_t* live[2];                            // ping-pong live lists
     int cur;
     int32_t* next_slots;                         // old slot of each survivor
@@ -182,12 +183,8 @@ int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
     ctx->err[0] = 0;
     const int n = cfg->n_classes, L = cfg->n_exits, B = cfg->max_batch;
     ctx->n_pad = round_up(n, kRowPad);
-    ctx->rows_pad = round_up(B, kRowPad);
-    ctx->Cp_max = 0;
-    for (int l = 0; l < L; ++l) {
-        ctx->Cp[l] = round_up(cfg->dims[l], kKPad);
-        if (ctx->Cp[l] > ctx->Cp_max) ctx->Cp_max = ctx->Cp[l];
-    }
+    ctx->tiles = (n + kScoreTileCols - 1) / kScoreTileCols;
+    for (int l = 0; l < L; ++l) ctx->Cp[l] = round_up(cfg->dims[l], kKPad);
 #define CREATE_TRY(expr)                                                                         \
     do {                                                                                         \
         hipError_t e_ = (expr);                                                                  \
@@ -205,16 +202,16 @@ int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
         CREATE_TRY(dev_alloc(ctx, &ctx->cinv[l], (size_t)n));
         CREATE_TRY(dev_alloc(ctx, &ctx->chat[l], (size_t)ctx->n_pad * ctx->Cp[l]));
         CREATE_TRY(dev_alloc(ctx, &ctx->mcount[l], (size_t)n));
-        CREATE_TRY(dev_alloc(ctx, &ctx->sv[l], (size_t)B * C));
+        CREATE_TRY(dev_alloc(ctx, &ctx->sv[l], (size_t)B * ctx->Cp[l]));
     }
     CREATE_TRY(dev_alloc(ctx, &ctx->FT, (size_t)n));
     CREATE_TRY(dev_alloc(ctx, &ctx->TS, (size_t)n));
     CREATE_TRY(dev_alloc(ctx, &ctx->hot_ids, (size_t)cfg->hot_max));
     CREATE_TRY(dev_alloc(ctx, &ctx->ids_stage, (size_t)cfg->hot_max));
-    CREATE_TRY(dev_alloc(ctx, &ctx->in_hot, (size_t)n));
-    CREATE_TRY(dev_alloc(ctx, &ctx->SA, (size_t)B * n));
-    CREATE_TRY(dev_alloc(ctx, &ctx->vinv, (size_t)B));
-    CREATE_TRY(dev_alloc(ctx, &ctx->vhat, (size_t)ctx->rows_pad * ctx->Cp_max));
+    CREATE_TRY(dev_alloc(ctx, &ctx->in_hot, (size_t)ctx->n_pad));
+    CREATE_TRY(dev_alloc(ctx, &ctx->SA, (size_t)B * n + kScoreTileCols));
+    CREATE_TRY(dev_alloc(ctx, &ctx->rowmax, (size_t)L * B * kRowMaxSlots));
+    CREATE_TRY(dev_alloc(ctx, &ctx->part, (size_t)ctx->tiles * 6 * B));
     CREATE_TRY(dev_alloc(ctx, &ctx->live[0], (size_t)B));
     CREATE_TRY(dev_alloc(ctx, &ctx->live[1], (size_t)B));
     CREATE_TRY(dev_alloc(ctx, &ctx->next_slots, (size_t)B));
@@ -242,15 +239,17 @@ int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
         CREATE_TRY(hipMemset(ctx->centres[l], 0, sizeof(float) * (size_t)n * cfg->dims[l]));
         CREATE_TRY(hipMemset(ctx->cinv[l], 0, sizeof(float) * (size_t)n));
         CREATE_TRY(hipMemset(ctx->chat[l], 0, sizeof(_Float16) * (size_t)ctx->n_pad * ctx->Cp[l]));
-        CREATE_TRY(hipMemset(ctx->sv[l], 0, sizeof(float) * (size_t)B * cfg->dims[l]));
+        CREATE_TRY(hipMemset(ctx->sv[l], 0, sizeof(float) * (size_t)B * ctx->Cp[l]));
         launch_fill_u32(ctx->mcount[l], (uint32_t)cfg->init_count, n, nullptr);
     }
     launch_fill_u32(reinterpret_cast<uint32_t*>(ctx->all_exits), (uint32_t)L, B, nullptr);
     CREATE_TRY(hipMemset(ctx->FT, 0, sizeof(uint32_t) * (size_t)n));
     CREATE_TRY(hipMemset(ctx->TS, 0, sizeof(uint32_t) * (size_t)n));
     CREATE_TRY(hipMemset(ctx->counts, 0, sizeof(Counts)));
-    CREATE_TRY(hipMemset(ctx->vhat, 0, sizeof(_Float16) * (size_t)ctx->rows_pad * ctx->Cp_max));
-    CREATE_TRY(hipMemset(ctx->SA, 0, sizeof(float) * (size_t)B * n));
+    CREATE_TRY(hipMemset(ctx->in_hot, 0, (size_t)ctx->n_pad));
+    CREATE_TRY(hipMemset(ctx->rowmax, 0, sizeof(uint32_t) * (size_t)L * B * kRowMaxSlots));
+    CREATE_TRY(hipMemset(ctx->part, 0, sizeof(float) * (size_t)ctx->tiles * 6 * B));
+    CREATE_TRY(hipMemset(ctx->SA, 0, sizeof(float) * ((size_t)B * n + kScoreTileCols)));
     CREATE_TRY(hipMemset(ctx->live[0], 0, sizeof(int32_t) * (size_t)B));
     CREATE_TRY(hipMemset(ctx->live[1], 0, sizeof(int32_t) * (size_t)B));
     CREATE_TRY(hipMemset(ctx->next_slots, 0, sizeof(int32_t) * (size_t)B));
@@ -380,11 +379,11 @@ int32_t smtm_begin_batch(smtm_ctx* ctx, int32_t batch, void* stream) {
         return fail(ctx, SMTM_ERR_SHAPE, "batch %d outside 1..max_batch (%d)", batch, ctx->cfg.max_batch);
     hipStream_t st = static_cast<hipStream_t>(stream);
     ctx->cur = 0;
-    launch_begin_batch(ctx->SA, ctx->cfg.n_classes, batch, ctx->live[0], ctx->res_layer, ctx->res_label,
-                       ctx->res_tier, ctx->counts, st);
+    launch_begin_batch(batch, ctx->live[0], ctx->res_layer, ctx->res_label, ctx->res_tier, ctx->counts, st);
     int32_t rc = check_launch(ctx, "smtm_begin_batch");
     if (rc) return rc;
     ctx->batch = batch;
+    ctx->sa_fresh = true;
     for (int l = 0; l < SMTM_MAX_EXITS; ++l) ctx->stage_done[l] = 0;
     return SMTM_OK;
 }
@@ -406,12 +405,14 @@ static int32_t encode_any(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int l = exit - 1;
+    uint32_t* rowmax = ctx->rowmax + (size_t)l * ctx->cfg.max_batch * kRowMaxSlots;
+    const EncodeOut out = {ctx->sv[l], ctx->Cp[l], sv_out, rowmax};
     if (channels_last)
         launch_encode_nhwc(fmap, dtype, ctx->cfg.dims[l], H * W, row_ids, ctx->live[ctx->cur], ctx->counts,
-                           ctx->batch, ctx->sv[l], sv_out, st, ctx->enc_kernel[l], sizeof(ctx->enc_kernel[l]));
+                           ctx->batch, out, st, ctx->enc_kernel[l], sizeof(ctx->enc_kernel[l]), &ctx->enc_slots[l]);
     else
         launch_encode(fmap, dtype, ctx->cfg.dims[l], H * W, row_ids, ctx->live[ctx->cur], ctx->counts, ctx->batch,
-                      ctx->sv[l], sv_out, st, ctx->enc_kernel[l], sizeof(ctx->enc_kernel[l]));
+                      out, st, ctx->enc_kernel[l], sizeof(ctx->enc_kernel[l]), &ctx->enc_slots[l]);
     rc = check_launch(ctx, "smtm_encode");
     if (rc) return rc;
     ctx->stage_done[l] = 1;
@@ -459,31 +460,40 @@ static CompactArgs compact_args(smtm_ctx* ctx, int32_t exit, int32_t* exit_ids, 
     return a;
 }
 
-// scores, SA accumulation, top-2 and decisions
-static void enqueue_lookup(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id, float* sims_out,
-                           hipStream_t st) {
+// scores, SA accumulation and the per-tile best / second best (one launch)
+static void enqueue_score(smtm_ctx* ctx, int32_t exit, float* sims_out, hipStream_t st) {
     const int l = exit - 1;
-    const int n = ctx->cfg.n_classes, C = ctx->cfg.dims[l], B = ctx->batch;
-    const int32_t* live = ctx->live[ctx->cur];
     int path = ctx->cfg.score_path;
     if (path == SMTM_SCORE_AUTO) path = ctx->enc_dtype[l] == SMTM_F16 ? SMTM_SCORE_MFMA : SMTM_SCORE_FP32;
-    const float weight = ldexpf(1.0f, exit - 1);
-    if (path == SMTM_SCORE_MFMA) {
-        launch_rownorm(ctx->sv[l], live, ctx->counts, B, C, ctx->vinv, ctx->vhat, ctx->Cp[l], st);
-        launch_score_mfma(ctx->vhat, ctx->chat[l], ctx->Cp[l], live, ctx->counts, B, n, weight, ctx->SA, sims_out, st);
-    } else {
-        launch_rownorm(ctx->sv[l], live, ctx->counts, B, C, ctx->vinv, nullptr, 0, st);
-        launch_score_fp32(ctx->sv[l], live, ctx->counts, B, ctx->vinv, ctx->centres[l], ctx->cinv[l], n, C, weight,
-                          ctx->SA, sims_out, st);
-    }
-    launch_top2_decide(ctx->SA, live, ctx->counts, B, n, ctx->in_hot, ctx->cfg.tiers, ctx->cfg.tau, ctx->decision,
-                       ctx->dlabel, ctx->top_val, ctx->top_id, top_val, top_id, st);
+    ScoreArgs a;
+    a.sv = ctx->sv[l]; a.ldv = ctx->Cp[l];
+    a.rowmax = ctx->rowmax + (size_t)l * ctx->cfg.max_batch * kRowMaxSlots;
+    a.rowmax_slots = ctx->enc_slots[l];
+    a.frame_ids = ctx->live[ctx->cur]; a.counts = ctx->counts; a.max_rows = ctx->batch;
+    a.n = ctx->cfg.n_classes; a.weight = ldexpf(1.0f, exit - 1);
+    a.first = ctx->sa_fresh ? 1 : 0;
+    a.SA = ctx->SA; a.sims_out = sims_out; a.in_hot = ctx->in_hot;
+    a.part = ctx->part; a.part_stride = ctx->cfg.max_batch;
+    if (path == SMTM_SCORE_MFMA) launch_score_mfma(a, ctx->chat[l], ctx->Cp[l], st);
+    else launch_score_fp32(a, ctx->centres[l], ctx->cinv[l], ctx->cfg.dims[l], st);
+    ctx->sa_fresh = false;
+}
+
+static DecideArgs decide_args(smtm_ctx* ctx, float* top_val, int32_t* top_id) {
+    DecideArgs g;
+    g.part = ctx->part; g.part_stride = ctx->cfg.max_batch; g.tiles = ctx->tiles;
+    g.counts = ctx->counts; g.max_rows = ctx->batch; g.tiers = ctx->cfg.tiers; g.tau = ctx->cfg.tau;
+    g.decision = ctx->decision; g.label = ctx->dlabel; g.top_val = ctx->top_val; g.top_id = ctx->top_id;
+    g.top_val_user = top_val; g.top_id_user = top_id;
+    return g;
 }
 
 int32_t smtm_lookup(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* top_id, float* sims_out, void* stream) {
     int32_t rc = check_lookup_state(ctx, exit, "smtm_lookup");
     if (rc) return rc;
-    enqueue_lookup(ctx, exit, top_val, top_id, sims_out, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    enqueue_score(ctx, exit, sims_out, st);
+    launch_decide(decide_args(ctx, top_val, top_id), st);
     rc = check_launch(ctx, "smtm_lookup");
     if (rc) return rc;
     ctx->stage_done[exit - 1] = 2;
@@ -531,8 +541,9 @@ int32_t smtm_lookup_exit(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* t
     rc = check_compact_args(ctx, live_ids, fmap_in, row_ids, fmap_out, row_bytes);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    enqueue_lookup(ctx, exit, top_val, top_id, nullptr, st);
-    launch_compact(compact_args(ctx, exit, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids, n_live_dev), st);
+    enqueue_score(ctx, exit, nullptr, st);
+    launch_decide_compact(decide_args(ctx, top_val, top_id),
+                          compact_args(ctx, exit, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids, n_live_dev), st);
     if (fmap_out)
         launch_gather_rows(fmap_in, row_ids, ctx->next_slots, ctx->counts, ctx->batch, fmap_out, row_bytes, st);
     rc = check_launch(ctx, "smtm_lookup_exit");

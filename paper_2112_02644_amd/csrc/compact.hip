@@ -4,46 +4,44 @@
 // wavefront, an LDS scan across the wavefronts of one block, running bases across chunks.
 // No atomics decide positions, so the lists come out in ascending frame id on every run.
 #include "internal.h"
+#include "decide.h"
 
 namespace smtm {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(256) void k_begin_batch(float* __restrict__ SA, int n, int batch,
-                                                     int32_t* __restrict__ live,
+// Start of a batch: identity live list, per-frame results and counters cleared.  The accumulated similarities
+// are not touched: the first lookup of the batch overwrites them.
+__global__ __launch_bounds__(256) void k_begin_batch(int batch, int32_t* __restrict__ live,
                                                      int32_t* __restrict__ res_layer,
                                                      int32_t* __restrict__ res_label,
                                                      int32_t* __restrict__ res_tier,
                                                      Counts* __restrict__ counts) {
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    const int64_t total = (int64_t)batch * n;
-    const int64_t quads = total >> 2;                    // SA comes from hipMalloc: 16-byte stores are aligned
-    u32x4* SA4 = reinterpret_cast<u32x4*>(SA);
-    for (int64_t i = tid; i < quads; i += stride) SA4[i] = u32x4{0u, 0u, 0u, 0u};
-    for (int64_t i = (quads << 2) + tid; i < total; i += stride) SA[i] = 0.f;
-    for (int64_t i = tid; i < batch; i += stride) {
-        live[i] = (int32_t)i;
+    const int tid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int stride = gridDim.x * blockDim.x;
+    for (int i = tid; i < batch; i += stride) {
+        live[i] = i;
         res_layer[i] = 0; res_label[i] = -1; res_tier[i] = 0;
     }
     if (tid == 0) { counts->n_live = batch; counts->n_exit = 0; }
     if (tid < SMTM_MAX_EXITS * 4) counts->stats[tid >> 2][tid & 3] = 0;
 }
 
-void launch_begin_batch(float* SA, int n, int batch, int32_t* live, int32_t* res_layer,
-                        int32_t* res_label, int32_t* res_tier, Counts* counts, hipStream_t st) {
-    int64_t total = (int64_t)batch * n;
-    int grid = (int)((total + 4095) / 4096);             // 256 threads x 16 bytes x 4 per block
-    if (grid > 2048) grid = 2048;
+void launch_begin_batch(int batch, int32_t* live, int32_t* res_layer, int32_t* res_label, int32_t* res_tier,
+                        Counts* counts, hipStream_t st) {
+    int grid = (batch + 255) / 256;
+    if (grid > 256) grid = 256;
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL(k_begin_batch, dim3(grid), dim3(256), 0, st, SA, n, batch, live, res_layer,
-                       res_label, res_tier, counts);
+    hipLaunchKernelGGL(k_begin_batch, dim3(grid), dim3(256), 0, st, batch, live, res_layer, res_label, res_tier,
+                       counts);
 }
 
 // Stable partition of the live list by one block: wavefront ballot + popcount prefix, an LDS scan
 // over the block's wavefronts, running bases across chunks of the list.
+// With `g` the decisions are not read from memory but made here, from the per-tile results of the scoring
+// kernel (and written out, with the top-2 values, as the stand-alone decision kernel would).
 template <int NW>                                        // wavefronts in the block
-__device__ __forceinline__ void compact_block(const CompactArgs& a) {
+__device__ __forceinline__ void compact_block(const CompactArgs& a, const DecideArgs* g) {
     __shared__ int w_exit[NW], w_t1[NW];
     __shared__ int base_exit, base_t1;
     constexpr int BS = NW * 64;
@@ -53,7 +51,10 @@ __device__ __forceinline__ void compact_block(const CompactArgs& a) {
     // max_rows entries.
     int n_live = a.counts->n_live;
     int d0 = 0, frame0 = 0, lab0 = -1;
-    if (tid < a.max_rows) { d0 = a.decision[tid]; frame0 = a.frame_ids[tid]; lab0 = a.label[tid]; }
+    if (tid < a.max_rows) {
+        frame0 = a.frame_ids[tid];
+        if (!g) { d0 = a.decision[tid]; lab0 = a.label[tid]; }
+    }
     asm volatile("" : "+v"(d0), "+v"(frame0), "+v"(lab0), "+s"(n_live));   // issued before any is waited for
     if (tid == 0) { base_exit = 0; base_t1 = 0; }
     __syncthreads();
@@ -63,7 +64,11 @@ __device__ __forceinline__ void compact_block(const CompactArgs& a) {
         int d = 0, frame = 0, lab = -1;
         if (valid) {
             if (c0 == 0) { d = d0; frame = frame0; lab = lab0; }
-            else { d = a.decision[slot]; frame = a.frame_ids[slot]; lab = a.label[slot]; }
+            else {
+                frame = a.frame_ids[slot];
+                if (!g) { d = a.decision[slot]; lab = a.label[slot]; }
+            }
+            if (g) { const SlotDecision sd = decide_slot(*g, slot); d = sd.d; lab = sd.label; }
         }
         const bool ex = valid && d != 0;
         const unsigned long long m_ex = __ballot(ex);
@@ -112,11 +117,21 @@ __device__ __forceinline__ void compact_block(const CompactArgs& a) {
 
 // One block of 1024 threads (16 wavefronts) walks the live list in chunks of 1024 slots.
 __global__ __launch_bounds__(1024) void k_compact(CompactArgs a) {
-    compact_block<16>(a);
+    compact_block<16>(a, nullptr);
 }
 
 void launch_compact(const CompactArgs& args, hipStream_t st) {
     hipLaunchKernelGGL(k_compact, dim3(1), dim3(1024), 0, st, args);
+}
+
+// Decision and compaction in one launch: each thread first merges its slot's per-tile results and applies
+// the exit rule, then the block partitions the live list.
+__global__ __launch_bounds__(1024) void k_decide_compact(DecideArgs g, CompactArgs a) {
+    compact_block<16>(a, &g);
+}
+
+void launch_decide_compact(const DecideArgs& g, const CompactArgs& args, hipStream_t st) {
+    hipLaunchKernelGGL(k_decide_compact, dim3(1), dim3(1024), 0, st, g, args);
 }
 
 // Gather of the survivors' feature-map rows: new slot s copies the row that old slot

@@ -33,46 +33,95 @@ struct CompactArgs {                      // everything the stable partition rea
 };
 
 constexpr int kWave = 64;
+constexpr int kRowMaxSlots = 64;          // partial maxima of |SV| kept per frame and exit point (one per bin of channel groups)
 constexpr int kKPad = 64;                 // fp16 operand rows are zero-padded to a multiple of this many columns
 constexpr int kRowPad = 128;              // fp16 operand matrices are padded to a multiple of this many rows
 
 static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
+// Where element (class j, channel c) of the unit fp16 copy of the centres lives.  The copy is kept in the order
+// the matrix cores take their B operand, so that a wavefront fetches the operand of one MFMA step (32 classes x
+// 16 channels, 1 KB) with one fully contiguous load: [class tile of 32][step of 16 channels][lane][8 halves],
+// where lane = 32 * (second half of the step's channels) + class within the tile.  Cp is a multiple of kKPad.
+__host__ __device__ static inline int64_t chat_index(int j, int c, int Cp) {
+    const int64_t step = (int64_t)(j >> 5) * (Cp >> 4) + (c >> 4);
+    return ((step * 64) + ((c >> 3) & 1) * 32 + (j & 31)) * 8 + (c & 7);
+}
+
 // ---- encode.hip -------------------------------------------------------------------------
 // Picks the streaming path from the shape; returns a short name of the path ("d16", "pair", "d8", "lds", "d4", "d2")
-// and writes the name of the kernel instance it launched to `name`.
+// and writes the name of the kernel instance it launched to `name` and the number of partial-maximum slots it fills
+// per frame to `slots`.
+struct EncodeOut {
+    float* sv;                            // [frames, ldv] by original frame id
+    int ldv;
+    float* sv_out;                        // [max_rows, C] by slot, or NULL
+    uint32_t* rowmax;                     // [frames, kRowMaxSlots] largest |SV| (bit pattern) per bin of the frame's channel groups
+};
 const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
                           const int32_t* frame_ids, const Counts* counts, int max_rows,
-                          float* sv_by_frame, float* sv_out_by_slot, hipStream_t st, char* name, size_t name_cap);
+                          const EncodeOut& out, hipStream_t st, char* name, size_t name_cap, int* slots);
 
 // Channels-last variant: fmap is [rows, H, W, C].
 const char* launch_encode_nhwc(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
                                const int32_t* frame_ids, const Counts* counts, int max_rows,
-                               float* sv_by_frame, float* sv_out_by_slot, hipStream_t st, char* name, size_t name_cap);
+                               const EncodeOut& out, hipStream_t st, char* name, size_t name_cap, int* slots);
 
 // ---- lookup.hip -------------------------------------------------------------------------
 void launch_centre_prepare(const float* centres, int n, int C, float* cinv, _Float16* chat, int Cp,
                            int row_lo, int row_hi, hipStream_t st);
-void launch_rownorm(const float* sv_by_frame, const int32_t* frame_ids, const Counts* counts,
-                    int max_rows, int C, float* vinv, _Float16* vhat, int Cp, hipStream_t st);
-void launch_score_fp32(const float* sv_by_frame, const int32_t* frame_ids, const Counts* counts,
-                       int max_rows, const float* vinv, const float* centres, const float* cinv,
-                       int n, int C, float weight, float* SA, float* sims_out, hipStream_t st);
-void launch_score_mfma(const _Float16* vhat, const _Float16* chat, int Cp, const int32_t* frame_ids,
-                       const Counts* counts, int max_rows, int n, float weight, float* SA,
-                       float* sims_out, hipStream_t st);
-void launch_top2_decide(const float* SA, const int32_t* frame_ids, const Counts* counts, int max_rows,
-                        int n, const uint8_t* in_hot, int tiers, float tau, int32_t* decision,
-                        int32_t* label, float* top_val, int32_t* top_id, float* top_val_user,
-                        int32_t* top_id_user, hipStream_t st);
+
+constexpr int kScoreTileRows = 32;        // live frames per scoring tile
+constexpr int kScoreTileCols = 128;       // classes per scoring tile (= kRowPad)
+
+struct ScoreArgs {
+    const float* sv;                      // [frames, ldv] fp32 semantic vectors by original frame id
+    int ldv;                              // row stride of sv (channels rounded up to kKPad, zero padded)
+    const uint32_t* rowmax;               // [frames, kRowMaxSlots] partial maxima of |SV| (bit patterns) at this exit point
+    int rowmax_slots;                     // how many of a frame's slots the encode kernel filled
+    const int32_t* frame_ids;             // [max_rows] live list
+    const Counts* counts;
+    int max_rows;
+    int n;                                // classes
+    float weight;                         // 2^(l-1)
+    int first;                            // 1: first lookup of the batch, SA holds nothing yet: SA = weight * s
+    float* SA;                            // [frames, n] by original frame id (with slack behind the last row)
+    float* sims_out;                      // [max_rows, n] by slot, or NULL
+    const uint8_t* in_hot;                // [n rounded up to kRowPad] fast-memory mask
+    float* part;                          // [tiles][6][part_stride] per-tile best / second best by slot
+    int part_stride;
+};
+void launch_score_mfma(const ScoreArgs& a, const _Float16* chat, int Cp, hipStream_t st);
+void launch_score_fp32(const ScoreArgs& a, const float* centres, const float* cinv, int C, hipStream_t st);
+
+struct DecideArgs {                       // merge of the per-tile results and the exit rule
+    const float* part;
+    int part_stride;
+    int tiles;
+    const Counts* counts;
+    int max_rows;
+    int tiers;
+    float tau;
+    int32_t* decision;                    // [max_rows] by slot: 0 continue, 1 / 2 released by tier 1 / 2
+    int32_t* label;                       // [max_rows]
+    float* top_val;                       // [max_rows, 2 tiers, 2]
+    int32_t* top_id;                      // [max_rows, 2 tiers]
+    float* top_val_user;                  // caller's copies, may be NULL
+    int32_t* top_id_user;
+};
+struct SlotDecision {
+    int d, label;
+};
+void launch_decide(const DecideArgs& g, hipStream_t st);
 
 void launch_separability(const float* sims, const Counts* counts, int max_rows, int n, const uint8_t* in_hot,
                          float* sep_out, hipStream_t st);
 
 // ---- compact.hip ------------------------------------------------------------------------
-void launch_begin_batch(float* SA, int n, int batch, int32_t* live, int32_t* res_layer,
-                        int32_t* res_label, int32_t* res_tier, Counts* counts, hipStream_t st);
+void launch_begin_batch(int batch, int32_t* live, int32_t* res_layer, int32_t* res_label, int32_t* res_tier,
+                        Counts* counts, hipStream_t st);
 void launch_compact(const CompactArgs& args, hipStream_t st);
+void launch_decide_compact(const DecideArgs& g, const CompactArgs& args, hipStream_t st);
 void launch_gather_rows(const void* src, const int32_t* row_ids, const int32_t* next_slots,
                         const Counts* counts, int max_rows, void* dst, int64_t row_bytes,
                         hipStream_t st);
@@ -88,9 +137,9 @@ struct CentreTables {                     // per exit point, passed by value to 
     uint32_t* mcount[SMTM_MAX_EXITS];
     float* cinv[SMTM_MAX_EXITS];
     _Float16* chat[SMTM_MAX_EXITS];
-    const float* sv[SMTM_MAX_EXITS];
+    const float* sv[SMTM_MAX_EXITS];      // [batch, Cp] saved semantic vectors by original frame id
     int C[SMTM_MAX_EXITS];
-    int Cp[SMTM_MAX_EXITS];
+    int Cp[SMTM_MAX_EXITS];               // channels rounded up to kKPad: row stride of chat and of sv
     const int32_t* res_layer;             // [batch] exit point at which the library released the frame, 0 = not released
     int enc_upto;                         // exit points 1..enc_upto have been encoded in this batch
 };

@@ -2,17 +2,23 @@
 // (arXiv 2112.02644, Eq. 1), accumulation over exit points with weight 2^(l-1) (Eq. 3), and per
 // memory tier the highest / second-highest accumulated similarity with the exit rule of Eq. 4.
 //
-// Everything read here (semantic vectors, centres, SA) is a few MB and stays in L2; the only
-// dense contraction is [live frames] x [classes] x [channels], which runs on the matrix cores
-// with unit-normalised fp16 operands and fp32 accumulation, or in fp32 vector arithmetic when
-// the feature maps are fp32.
+// Two launches per exit point:
+//   score    one block per tile of 32 live frames x 128 classes.  It reads the frames' fp32 semantic
+//            vectors and the centres (a few MB, from L2), takes the length of the vectors from the same
+//            loads, contracts on the matrix cores (fp16 operands, fp32 accumulation) or in fp32 vector
+//            arithmetic, updates SA in its epilogue and leaves, per frame and tile, the best and second
+//            best SA of each memory tier.
+//   decide   merges a frame's per-tile partial results in tile order and applies the exit rule; either as
+//            a kernel of its own or at the head of the compaction kernel (compact.hip).
 #include "internal.h"
+#include "decide.h"
 
 namespace smtm {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float wave_sum(float x) {
     for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
@@ -25,7 +31,8 @@ __device__ __forceinline__ float inv_norm_of(float nrm2) {
     return 1.0f / sqrtf(nrm2);
 }
 
-// One wavefront per class: 1/|SC_j| and the unit-normalised fp16 copy [n_pad, Cp] (zero padded).
+// One wavefront per class: 1/|SC_j| and the unit-normalised fp16 copy (n_pad classes x Cp channels, zero
+// padded, in the operand order of chat_index).
 __global__ __launch_bounds__(256) void k_centre_prepare(const float* __restrict__ centres, int n, int C,
                                                         float* __restrict__ cinv,
                                                         _Float16* __restrict__ chat, int Cp,
@@ -34,7 +41,7 @@ __global__ __launch_bounds__(256) void k_centre_prepare(const float* __restrict_
     const int j = row_lo + blockIdx.x * 4 + (threadIdx.x >> 6);
     if (j >= row_hi) return;
     if (j >= n) {                                       // padding rows of the fp16 copy
-        for (int c = lane; c < Cp; c += 64) chat[(int64_t)j * Cp + c] = (_Float16)0.f;
+        for (int c = lane; c < Cp; c += 64) chat[chat_index(j, c, Cp)] = (_Float16)0.f;
         return;
     }
     const float* p = centres + (int64_t)j * C;
@@ -46,7 +53,7 @@ __global__ __launch_bounds__(256) void k_centre_prepare(const float* __restrict_
     for (int c = lane; c < Cp; c += 64) {
         float x = 0.f;
         if (c < C && inv != 0.f) x = p[c] * inv;
-        chat[(int64_t)j * Cp + c] = (_Float16)x;
+        chat[chat_index(j, c, Cp)] = (_Float16)x;
     }
 }
 
@@ -58,456 +65,400 @@ void launch_centre_prepare(const float* centres, int n, int C, float* cinv, _Flo
                        chat, Cp, row_lo, row_hi);
 }
 
-// One wavefront per live slot: 1/|SV| and (optionally) the unit-normalised fp16 row for the MFMA
-// path.  The row is read with 16-byte loads, four per lane in flight, when C is a multiple of 4.
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
-
-__global__ __launch_bounds__(256) void k_rownorm(const float* __restrict__ sv,
-                                                 const int32_t* __restrict__ frame_ids,
-                                                 const Counts* __restrict__ counts, int max_rows, int C,
-                                                 float* __restrict__ vinv, _Float16* __restrict__ vhat,
-                                                 int Cp) {
-    const int lane = threadIdx.x & 63;
-    int slot = blockIdx.x * 4 + (threadIdx.x >> 6);
-    // The first slot's frame id is fetched together with the live count: both come from memory written by
-    // the kernel before, and one after the other they would cost two round trips.  The list has max_rows
-    // entries, all of them frame ids of this or an earlier batch.
-    int n_live = counts->n_live;
-    int fid = slot < max_rows ? frame_ids[slot] : 0;
-    asm volatile("" : "+v"(fid), "+s"(n_live));          // both loads are issued before either is waited for
-    if (n_live > max_rows) n_live = max_rows;
-    const int n_waves = gridDim.x * 4;
-    const bool vec = (C & 3) == 0;
-    for (; slot < n_live; slot += n_waves, fid = slot < n_live ? frame_ids[slot] : 0) {
-        const float* p = sv + (int64_t)fid * C;
-        float ss = 0.f;
-        if (vec && Cp <= 2048) {
-            // the row stays in registers between the norm and the fp16 copy (at most 8 x 16 bytes per lane)
-            const f32x4* p4 = reinterpret_cast<const f32x4*>(p);
-            const int nq = C >> 2, nqp = Cp >> 2;           // Cp is a multiple of 64
-            f32x4 x[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int q = u * 64 + lane;
-                x[u] = q < nq ? p4[q] : f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                ss += (x[u].x * x[u].x + x[u].y * x[u].y) + (x[u].z * x[u].z + x[u].w * x[u].w);
-            ss = wave_sum(ss);
-            const float inv = inv_norm_of(ss);
-            if (lane == 0) vinv[slot] = inv;
-            if (vhat) {
-                _Float16* out = vhat + (int64_t)slot * Cp;
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int q = u * 64 + lane;
-                    if (q < nqp) {
-                        f32x4 y = {0.f, 0.f, 0.f, 0.f};     // a zero or non-finite row (inv = 0) becomes zeros, as the padding
-                        if (inv != 0.f) y = x[u] * inv;
-                        const half4_t h = {(_Float16)y.x, (_Float16)y.y, (_Float16)y.z, (_Float16)y.w};
-                        *reinterpret_cast<half4_t*>(out + 4 * q) = h;
-                    }
-                }
-            }
-            continue;
-        }
-        if (vec) {
-            const f32x4* p4 = reinterpret_cast<const f32x4*>(p);
-            const int nq = C >> 2;
-            for (int base = 0; base < nq; base += 256) {
-                f32x4 x[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int q = base + u * 64 + lane;
-                    x[u] = q < nq ? p4[q] : f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    ss += (x[u].x * x[u].x + x[u].y * x[u].y) + (x[u].z * x[u].z + x[u].w * x[u].w);
-            }
-        } else {
-            for (int c = lane; c < C; c += 64) { const float x = p[c]; ss += x * x; }
-        }
-        ss = wave_sum(ss);
-        const float inv = inv_norm_of(ss);
-        if (lane == 0) vinv[slot] = inv;
-        if (vhat) {
-            _Float16* out = vhat + (int64_t)slot * Cp;
-            if (vec) {
-                const f32x4* p4 = reinterpret_cast<const f32x4*>(p);
-                const int nq = C >> 2, nqp = Cp >> 2;       // Cp is a multiple of 64
-                for (int q = lane; q < nqp; q += 64) {
-                    f32x4 x = {0.f, 0.f, 0.f, 0.f};
-                    if (q < nq && inv != 0.f) x = p4[q] * inv;
-                    half4_t h = {(_Float16)x.x, (_Float16)x.y, (_Float16)x.z, (_Float16)x.w};
-                    *reinterpret_cast<half4_t*>(out + 4 * q) = h;
-                }
-            } else {
-                for (int c = lane; c < Cp; c += 64) {
-                    float x = 0.f;
-                    if (c < C && inv != 0.f) x = p[c] * inv;
-                    out[c] = (_Float16)x;
-                }
-            }
-        }
-    }
-}
-
-void launch_rownorm(const float* sv, const int32_t* frame_ids, const Counts* counts, int max_rows,
-                    int C, float* vinv, _Float16* vhat, int Cp, hipStream_t st) {
-    int grid = (max_rows + 3) / 4;
-    if (grid > 2048) grid = 2048;
-    hipLaunchKernelGGL(k_rownorm, dim3(grid), dim3(256), 0, st, sv, frame_ids, counts, max_rows, C, vinv,
-                       vhat, Cp);
-}
-
 // ---------------------------------------------------------------------------------------------
-// fp32 scoring: 64 slots x 64 classes per block, 4 x 4 per thread, K staged through LDS.
-// s = <SV, SC_j> * (1/|SV|) * (1/|SC_j|);  SA[frame][j] += weight * s.
-constexpr int FT_M = 64, FT_N = 64, FT_K = 16;
-
-__global__ __launch_bounds__(256) void k_score_fp32(
-    const float* __restrict__ sv, const int32_t* __restrict__ frame_ids,
-    const Counts* __restrict__ counts, int max_rows, const float* __restrict__ vinv,
-    const float* __restrict__ centres, const float* __restrict__ cinv, int n, int C, float weight,
-    float* __restrict__ SA, float* __restrict__ sims_out) {
-    __shared__ float As[FT_K][FT_M + 4];
-    __shared__ float Bs[FT_K][FT_N + 4];
-    int n_live = counts->n_live;
-    if (n_live > max_rows) n_live = max_rows;
-    const int m0 = blockIdx.y * FT_M, n0 = blockIdx.x * FT_N;
-    if (m0 >= n_live) return;                            // uniform over the block
-    const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
-    const int lr = tid >> 2, lk = (tid & 3) * 4;         // loader: row 0..63, k offset 0,4,8,12
-    const int a_slot = m0 + lr, b_cls = n0 + lr;
-    const float* a_ptr = a_slot < n_live ? sv + (int64_t)frame_ids[a_slot] * C : nullptr;
-    const float* b_ptr = b_cls < n ? centres + (int64_t)b_cls * C : nullptr;
-    float acc[4][4] = {};
-    for (int k0 = 0; k0 < C; k0 += FT_K) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int k = k0 + lk + i;
-            As[lk + i][lr] = (a_ptr && k < C) ? a_ptr[k] : 0.f;
-            Bs[lk + i][lr] = (b_ptr && k < C) ? b_ptr[k] : 0.f;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < FT_K; ++kk) {
-            float a[4], b[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
-        }
-        __syncthreads();
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int slot = m0 + ty * 4 + i;
-        if (slot >= n_live) continue;
-        const float vi = vinv[slot];
-        const int64_t frame = frame_ids[slot];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int cls = n0 + tx * 4 + j;
-            if (cls >= n) continue;
-            const float ci = cinv[cls];
-            float s = acc[i][j] * vi * ci;
-            if (vi == 0.f || ci == 0.f || !(fabsf(s) < __builtin_inff())) s = 0.f;
-            SA[frame * n + cls] += weight * s;
-            if (sims_out) sims_out[(int64_t)slot * n + cls] = s;
-        }
-    }
-}
-
-void launch_score_fp32(const float* sv, const int32_t* frame_ids, const Counts* counts, int max_rows,
-                       const float* vinv, const float* centres, const float* cinv, int n, int C,
-                       float weight, float* SA, float* sims_out, hipStream_t st) {
-    dim3 grid((n + FT_N - 1) / FT_N, (max_rows + FT_M - 1) / FT_M);
-    hipLaunchKernelGGL(k_score_fp32, grid, dim3(256), 0, st, sv, frame_ids, counts, max_rows, vinv,
-                       centres, cinv, n, C, weight, SA, sims_out);
-}
-
-// ---------------------------------------------------------------------------------------------
-// MFMA scoring.  A = unit fp16 semantic vectors by slot [rows_pad, Cp], B = unit fp16 centres
-// [n_pad, Cp], both K-contiguous and zero padded, so S = A * B^T needs no bounds checks inside
-// the K loop.  Block = 4 wavefronts as 2 x 2, each wavefront one 32x32 tile per (WM, WN) repeat,
-// v_mfma_f32_32x32x16_f16: lane holds A[row = lane%32][k = 8*(lane/32) .. +7] and the same for
-// B by column; acc[i] is C[row = 8*(i/4) + 4*(lane/32) + i%4][col = lane%32].
-constexpr int MF_K = 64;                 // K per LDS stage
-constexpr int MF_LD = MF_K + 8;          // padded LDS row (halves): 144 B keeps 16-byte reads conflict-free
-
-template <int WM, int WN>
-__global__ __launch_bounds__(256) void k_score_mfma(
-    const _Float16* __restrict__ A, const _Float16* __restrict__ B, int Cp,
-    const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows, int n,
-    float weight, float* __restrict__ SA, float* __restrict__ sims_out) {
-    constexpr int BM = 64 * WM, BN = 64 * WN;
-    constexpr int RA = BM / 32, RB = BN / 32;            // 16-byte chunks each thread moves per stage
-    __shared__ _Float16 As[2][BM * MF_LD];               // double buffered: the next K stage is fetched
-    __shared__ _Float16 Bs[2][BN * MF_LD];               // from L2 while the current one is multiplied
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int lrow = lane & 31, lk = (lane >> 5) * 8;
-
-    floatx16 acc[WM][WN];
-#pragma unroll
-    for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    // loader: each 64-half row of a stage is 8 chunks of 16 B; thread -> (row, chunk)
-    const int ld_row = tid >> 3, ld_chunk = tid & 7;
-    const _Float16* a_src = A + (int64_t)(m0 + ld_row) * Cp + ld_chunk * 8;
-    const _Float16* b_src = B + (int64_t)(n0 + ld_row) * Cp + ld_chunk * 8;
-    const int lds_off = ld_row * MF_LD + ld_chunk * 8;
-    // Four register sets: while stage st is multiplied out of LDS, the loads of stages st+2 .. st+4 are
-    // in flight and stage st+1 (loaded three iterations earlier) is written to the other LDS buffer.
-    // A stage is 16 KB per block from L2 or beyond; with fewer stages in flight the K loop runs at the
-    // pace of that latency.
-    u32x4 ra0[RA], rb0[RB], ra1[RA], rb1[RB], ra2[RA], rb2[RB], ra3[RA], rb3[RB];
-    const int n_stage = Cp / MF_K;
-    auto fetch = [&](u32x4* ra, u32x4* rb, int stage) {
-        const int k1 = stage * MF_K;
-#pragma unroll
-        for (int r = 0; r < RA; ++r) ra[r] = *reinterpret_cast<const u32x4*>(a_src + (int64_t)r * 32 * Cp + k1);
-#pragma unroll
-        for (int r = 0; r < RB; ++r) rb[r] = *reinterpret_cast<const u32x4*>(b_src + (int64_t)r * 32 * Cp + k1);
-    };
-    auto stash = [&](const u32x4* ra, const u32x4* rb, int buf) {
-#pragma unroll
-        for (int r = 0; r < RA; ++r) *reinterpret_cast<u32x4*>(&As[buf][lds_off + r * 32 * MF_LD]) = ra[r];
-#pragma unroll
-        for (int r = 0; r < RB; ++r) *reinterpret_cast<u32x4*>(&Bs[buf][lds_off + r * 32 * MF_LD]) = rb[r];
-    };
-    auto multiply = [&](int buf) {
-#pragma unroll
-        for (int ks = 0; ks < MF_K; ks += 16) {
-            half8_t a[WM], b[WN];
-#pragma unroll
-            for (int i = 0; i < WM; ++i)
-                a[i] = *reinterpret_cast<const half8_t*>(&As[buf][((wm * WM + i) * 32 + lrow) * MF_LD + ks + lk]);
-#pragma unroll
-            for (int j = 0; j < WN; ++j)
-                b[j] = *reinterpret_cast<const half8_t*>(&Bs[buf][((wn * WN + j) * 32 + lrow) * MF_LD + ks + lk]);
-#pragma unroll
-            for (int i = 0; i < WM; ++i)
-#pragma unroll
-                for (int j = 0; j < WN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-    };
-    // the operand loads are in bounds whatever the live count is (padded matrices), so they are
-    // issued before the live count is waited for
-    fetch(ra0, rb0, 0);
-    if (n_stage > 1) fetch(ra1, rb1, 1);
-    if (n_stage > 2) fetch(ra2, rb2, 2);
-    if (n_stage > 3) fetch(ra3, rb3, 3);
-    // Frame ids of this thread's output rows, then the old SA values of its outputs: two batches of
-    // loads (all ids, then all values) that complete under the K loop.  Indices are clamped into the
-    // buffers so that no load sits behind a branch (one behind a branch waits for the one before it,
-    // and sixteen such pairs in a row cost more than the whole contraction); the list holds max_rows
-    // frame ids of this or an earlier batch, so every address is inside SA, and what is fetched for
-    // rows or classes outside the live tile is never used.
-    int fid[WM][16];
-#pragma unroll
-    for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int slot = m0 + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-            fid[i][e] = frame_ids[slot < max_rows ? slot : max_rows - 1];
-        }
-    int n_live = counts->n_live;
-    if (n_live > max_rows) n_live = max_rows;
-    if (m0 >= n_live) return;                            // uniform over the block
-    stash(ra0, rb0, 0);
-    __syncthreads();
-
-    float sa_old[WM][WN][16];
-#pragma unroll
-    for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j) {
-            const int cls = n0 + (wn * WN + j) * 32 + (lane & 31);
-            const int cc = cls < n ? cls : n - 1;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) sa_old[i][j][e] = SA[(int64_t)fid[i][e] * n + cc];
-        }
-
-    for (int st = 0; st < n_stage; st += 4) {            // four stages per trip so the register sets are static
-        // stage st: LDS buffer 0 holds it; set 0 is free, sets 1..3 hold stages st+1 .. st+3
-        if (st + 4 < n_stage) fetch(ra0, rb0, st + 4);
-        multiply(0);
-        if (st + 1 < n_stage) stash(ra1, rb1, 1);        // buffer 1 was last read before the previous barrier
-        __syncthreads();
-        if (st + 1 >= n_stage) break;                    // uniform
-        // stage st+1: buffer 1
-        if (st + 5 < n_stage) fetch(ra1, rb1, st + 5);
-        multiply(1);
-        if (st + 2 < n_stage) stash(ra2, rb2, 0);
-        __syncthreads();
-        if (st + 2 >= n_stage) break;
-        // stage st+2: buffer 0
-        if (st + 6 < n_stage) fetch(ra2, rb2, st + 6);
-        multiply(0);
-        if (st + 3 < n_stage) stash(ra3, rb3, 1);
-        __syncthreads();
-        if (st + 3 >= n_stage) break;
-        // stage st+3: buffer 1
-        if (st + 7 < n_stage) fetch(ra3, rb3, st + 7);
-        multiply(1);
-        if (st + 4 < n_stage) stash(ra0, rb0, 0);
-        __syncthreads();
-    }
-
-#pragma unroll
-    for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j) {
-            const int cls = n0 + (wn * WN + j) * 32 + (lane & 31);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int slot = m0 + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                if (slot < n_live && cls < n) {
-                    const float s = acc[i][j][e];
-                    SA[(int64_t)fid[i][e] * n + cls] = sa_old[i][j][e] + weight * s;
-                    if (sims_out) sims_out[(int64_t)slot * n + cls] = s;
-                }
-            }
-        }
-}
-
-void launch_score_mfma(const _Float16* vhat, const _Float16* chat, int Cp, const int32_t* frame_ids,
-                       const Counts* counts, int max_rows, int n, float weight, float* SA,
-                       float* sims_out, hipStream_t st) {
-    // operands are padded to kRowPad rows, so a 64x64 block tile never reads outside them
-    dim3 grid((n + 63) / 64, (max_rows + 63) / 64);
-    hipLaunchKernelGGL((k_score_mfma<1, 1>), grid, dim3(256), 0, st, vhat, chat, Cp, frame_ids, counts,
-                       max_rows, n, weight, SA, sims_out);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Top-2 per tier and the exit rule.  One wavefront per live slot walks its SA row.
-struct Top2 {
-    float v1; int id1; float v2;
+// What the scoring kernels share.
+//
+// Length of a semantic vector without a pass of its own: the encode kernels leave the largest |SV| of
+// every frame (as the bit pattern of a non-negative float, which orders like the value).  From it a power
+// of two is taken that brings the largest component into [1, 4), every component is multiplied by it
+// (exact), and the sum of squares of the scaled components is accumulated from the very loads that feed
+// the contraction.  The scaled components fit fp16 whatever the magnitude of the feature maps was, and
+// the sum of squares can neither overflow nor vanish.
+struct RowScale {
+    float scale;                                         // power of two, 0 for a dead row
+    bool dead;                                           // zero or non-finite vector: every similarity is 0
 };
 
-// The order is (larger value first, then smaller class id); id < 0 with value -inf marks "no entry".
-// Accumulated similarities are finite, so -inf never is a real entry.  Everything below is written with
-// selects: as nested branches the per-element update cost several times the memory traffic of the row.
-
-// One more entry for a lane's running top-2.  A lane meets its classes in ascending id, so an equal value
-// never displaces the best one (strict >).  `take` = false leaves the triple as it is.
-__device__ __forceinline__ void top2_push(Top2& t, float v, int id, bool take = true) {
-    const float x = take ? v : -__builtin_inff();
-    const bool gt = x > t.v1;
-    t.v2 = gt ? t.v1 : fmaxf(t.v2, x);
-    t.id1 = gt ? id : t.id1;
-    t.v1 = gt ? x : t.v1;
+__device__ __forceinline__ RowScale row_scale_of(uint32_t max_bits) {
+    RowScale r;
+    r.dead = max_bits == 0u || max_bits >= 0x7f800000u;
+    int field = 254 - (int)(max_bits >> 23);             // exponent field of 2^(127 - e): max * scale in [1, 2)
+    field = field < 1 ? 1 : (field > 253 ? 253 : field);
+    r.scale = r.dead ? 0.f : __builtin_bit_cast(float, (uint32_t)field << 23);
+    return r;
 }
 
-// Merge of another lane's (best, id, second) triple; the second of a triple never exceeds its best.
-__device__ __forceinline__ void top2_merge(Top2& t, float v1, int id1, float v2) {
-    // ids compare as unsigned so that "no entry" (-1) loses a tie of two -inf against nothing real
-    const bool b = (v1 > t.v1) | ((v1 == t.v1) & ((uint32_t)id1 < (uint32_t)t.id1));
-    const float loser = b ? t.v1 : v1;
-    t.v2 = fmaxf(fmaxf(t.v2, v2), loser);
-    t.v1 = b ? v1 : t.v1;
-    t.id1 = b ? id1 : t.id1;
+// Largest |SV| of the frame of an epilogue row: thread (row = tid/8, k = tid%8) looks at the frame's slots
+// 8k .. 8k+7 (the encode kernel filled the first `slots` of the kRowMaxSlots = 64) and the 8 threads of the row combine.
+__device__ __forceinline__ uint32_t row_max_bits(const uint32_t* __restrict__ rowmax, int slots, int fid) {
+    const int k = threadIdx.x & 7;
+    const u32x4* p = reinterpret_cast<const u32x4*>(rowmax + (int64_t)fid * kRowMaxSlots + 8 * k);
+    const u32x4 lo = p[0], hi = p[1];
+    uint32_t a = 0u;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t x = 8 * k + e < slots ? lo[e] : 0u, y = 8 * k + 4 + e < slots ? hi[e] : 0u;
+        a = x > a ? x : a;
+        a = y > a ? y : a;
+    }
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)a, off, 64);
+        a = o > a ? o : a;
+    }
+    return a;
 }
 
-__device__ __forceinline__ bool exit_rule(float h, float sh, float tau) {
-    if (!(h > 0.f)) return false;
-    if (sh == -__builtin_inff()) return false;           // fewer than two entries in the tier
-    const float runner = sh > 0.f ? sh : 0.f;
-    return (h - sh) > tau * runner;
-}
+constexpr int SC_M = kScoreTileRows;                     // live frames per block tile
+constexpr int SC_N = kScoreTileCols;                     // classes per block tile
+constexpr int SC_LD = SC_N + 4;                          // padded LDS row (floats)
 
-__global__ __launch_bounds__(256) void k_top2_decide(
-    const float* __restrict__ SA, const int32_t* __restrict__ frame_ids,
-    const Counts* __restrict__ counts, int max_rows, int n, const uint8_t* __restrict__ in_hot,
-    int tiers, float tau, int32_t* __restrict__ decision, int32_t* __restrict__ label,
-    float* __restrict__ top_val, int32_t* __restrict__ top_id, float* __restrict__ top_val_user,
-    int32_t* __restrict__ top_id_user) {
-    const int lane = threadIdx.x & 63;
-    int slot = blockIdx.x * 4 + (threadIdx.x >> 6);
-    int n_live = counts->n_live;
-    int fid = slot < max_rows ? frame_ids[slot] : 0;      // fetched together with the live count, as in k_rownorm
-    asm volatile("" : "+v"(fid), "+s"(n_live));
-    if (n_live > max_rows) n_live = max_rows;
-    const int n_waves = gridDim.x * 4;
+// Epilogue of a 32 x 128 tile whose dot products (of the scaled semantic vectors with the centre rows) sit in
+// LDS as `copies` partial sums.  Thread t owns frame t/8 of the tile and 16 consecutive classes.
+//   s = dot * inv_len(frame) * col_scale;   SA = SA_old + weight * s   (Eq. 1, Eq. 3)
+// then the best / second best SA of the thread's classes per tier, merged over the 8 threads of the frame.
+// sa_old holds the thread's 16 old SA values and hotw the fast-memory mask bytes of its 16 classes (both fetched
+// before the contraction; sa_old is ignored when a.first).
+__device__ __forceinline__ void score_epilogue(const ScoreArgs& a, const float* red, int copies, float ss,
+                                               bool dead, const float* cinv, u32x4 hotw, int m0, int n0, int n_live,
+                                               int fid, const f32x4 (&sa_old)[4]) {
+    const int tid = threadIdx.x;
+    const int row = tid >> 3, cg = tid & 7;
+    const int slot = m0 + row;
+    const bool live = slot < n_live;
+    const int cls0 = n0 + cg * 16;
+    float inv = inv_norm_of(ss);
+    if (dead) inv = 0.f;
+    float v[16];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        f32x4 acc = *reinterpret_cast<const f32x4*>(red + row * SC_LD + cg * 16 + 4 * q);
+        for (int w = 1; w < copies; ++w)                 // fixed order: the result does not depend on scheduling
+            acc += *reinterpret_cast<const f32x4*>(red + (w * SC_M + row) * SC_LD + cg * 16 + 4 * q);
+        v[4 * q] = acc.x; v[4 * q + 1] = acc.y; v[4 * q + 2] = acc.z; v[4 * q + 3] = acc.w;
+    }
     const float ninf = -__builtin_inff();
-    const bool vec = (n & 3) == 0;
-    for (; slot < n_live; slot += n_waves, fid = slot < n_live ? frame_ids[slot] : 0) {
-        const float* row = SA + (int64_t)fid * n;
-        Top2 hot = {ninf, -1, ninf}, all = {ninf, -1, ninf};
-        if (vec) {
-            // each lane takes 4 consecutive classes per access, four accesses in flight
-            const f32x4* row4 = reinterpret_cast<const f32x4*>(row);
-            const uint32_t* hot4 = reinterpret_cast<const uint32_t*>(in_hot);
-            const int nq = n >> 2;
-            for (int base = 0; base < nq; base += 256) {
-                f32x4 x[4];
-                uint32_t h[4];
+    Top2 hot = {ninf, -1, ninf}, all = {ninf, -1, ninf};
+    float* sa_row = a.SA + (int64_t)fid * a.n;
+    float sa_new[16];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int q = base + u * 64 + lane;
-                    if (q < nq) { x[u] = row4[q]; h[u] = hot4[q]; }
-                }
+    for (int i = 0; i < 16; ++i) {
+        const int cls = cls0 + i;
+        float s = v[i] * inv;
+        if (cinv) s *= cinv[cls < a.n ? cls : a.n - 1];
+        if (inv == 0.f || !(fabsf(s) < __builtin_inff())) s = 0.f;
+        v[i] = s;
+        const float old = a.first ? 0.f : sa_old[i >> 2][i & 3];
+        sa_new[i] = old + a.weight * s;
+        const bool in = cls < a.n;
+        const bool h = ((hotw[i >> 2] >> (8 * (i & 3))) & 0xffu) != 0;
+        top2_push(all, sa_new[i], cls, in);
+        top2_push(hot, sa_new[i], cls, in && h);
+    }
+    if (live) {
+        const bool vec = (a.n & 3) == 0;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int q = base + u * 64 + lane;
-                    if (q < nq) {
+        for (int q = 0; q < 4; ++q) {
+            const int cls = cls0 + 4 * q;
+            if (vec && cls + 3 < a.n) {
+                *reinterpret_cast<f32x4*>(sa_row + cls) = f32x4{sa_new[4 * q], sa_new[4 * q + 1], sa_new[4 * q + 2], sa_new[4 * q + 3]};
+                if (a.sims_out)
+                    *reinterpret_cast<f32x4*>(a.sims_out + (int64_t)slot * a.n + cls) = f32x4{v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+            } else {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            top2_push(all, x[u][e], 4 * q + e);
-                            top2_push(hot, x[u][e], 4 * q + e, ((h[u] >> (8 * e)) & 0xffu) != 0);
-                        }
+                for (int e = 0; e < 4; ++e)
+                    if (cls + e < a.n) {
+                        sa_row[cls + e] = sa_new[4 * q + e];
+                        if (a.sims_out) a.sims_out[(int64_t)slot * a.n + cls + e] = v[4 * q + e];
                     }
-                }
-            }
-        } else {
-            for (int j = lane; j < n; j += 64) {
-                const float x = row[j];
-                top2_push(all, x, j);
-                top2_push(hot, x, j, in_hot[j] != 0);
             }
         }
-        for (int off = 32; off > 0; off >>= 1) {
-            float v1 = __shfl_xor(all.v1, off, 64); int id1 = __shfl_xor(all.id1, off, 64);
-            float v2 = __shfl_xor(all.v2, off, 64);
-            top2_merge(all, v1, id1, v2);
-            v1 = __shfl_xor(hot.v1, off, 64); id1 = __shfl_xor(hot.id1, off, 64);
-            v2 = __shfl_xor(hot.v2, off, 64);
-            top2_merge(hot, v1, id1, v2);
-        }
-        if (lane == 0) {
-            int d = 0, lab = -1;
-            if (exit_rule(hot.v1, hot.v2, tau)) { d = 1; lab = hot.id1; }
-            else if (tiers == 2 && exit_rule(all.v1, all.v2, tau)) { d = 2; lab = all.id1; }
-            if (tiers != 2) { all.v1 = ninf; all.v2 = ninf; all.id1 = -1; }
-            decision[slot] = d;
-            label[slot] = lab;
-            float* tv = top_val + (int64_t)slot * 4;
-            tv[0] = hot.v1; tv[1] = hot.v2; tv[2] = all.v1; tv[3] = all.v2;
-            top_id[slot * 2] = hot.id1; top_id[slot * 2 + 1] = all.id1;
-            if (top_val_user) {
-                float* u = top_val_user + (int64_t)slot * 4;
-                u[0] = hot.v1; u[1] = hot.v2; u[2] = all.v1; u[3] = all.v2;
-            }
-            if (top_id_user) { top_id_user[slot * 2] = hot.id1; top_id_user[slot * 2 + 1] = all.id1; }
-        }
+    }
+    // the 8 threads of a frame hold its classes in ascending order of cg; merge in a fixed butterfly
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) {
+        float v1 = __shfl_xor(all.v1, off, 64); int id1 = __shfl_xor(all.id1, off, 64);
+        float v2 = __shfl_xor(all.v2, off, 64);
+        top2_merge(all, v1, id1, v2);
+        v1 = __shfl_xor(hot.v1, off, 64); id1 = __shfl_xor(hot.id1, off, 64);
+        v2 = __shfl_xor(hot.v2, off, 64);
+        top2_merge(hot, v1, id1, v2);
+    }
+    if (live && cg == 0) {
+        float* p = a.part + (int64_t)blockIdx.x * SC_FIELDS * a.part_stride + slot;
+        p[0] = hot.v1;
+        p[a.part_stride] = __builtin_bit_cast(float, hot.id1);
+        p[2 * (int64_t)a.part_stride] = hot.v2;
+        p[3 * (int64_t)a.part_stride] = all.v1;
+        p[4 * (int64_t)a.part_stride] = __builtin_bit_cast(float, all.id1);
+        p[5 * (int64_t)a.part_stride] = all.v2;
     }
 }
 
+// Old SA values of the thread's 16 classes.  The buffer has slack behind its last row, and the frame id comes
+// from a list that only holds ids of this or an earlier batch, so the loads need no bounds checks.
+__device__ __forceinline__ void fetch_sa_old(const ScoreArgs& a, int fid, int n0, f32x4 (&sa_old)[4]) {
+    const int cg = threadIdx.x & 7;
+    const float* sa_row = a.SA + (int64_t)fid * a.n + n0 + cg * 16;
+    if (a.first) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sa_old[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    } else if ((a.n & 3) == 0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sa_old[q] = *reinterpret_cast<const f32x4*>(sa_row + 4 * q);
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sa_old[q] = f32x4{sa_row[4 * q], sa_row[4 * q + 1], sa_row[4 * q + 2], sa_row[4 * q + 3]};
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// MFMA scoring.  v_mfma_f32_32x32x16_f16: a lane holds A[row = lane%32][k = 8*(lane/32) .. +7] and the same of B
+// by column; acc[e] is C[row = 8*(e/4) + 4*(lane/32) + e%4][col = lane%32].
+//   B (centres) is stored in exactly that order (chat_index), so the operand of a step is one contiguous 1 KB
+//     load per wavefront, straight from L2 into registers.
+//   A (semantic vectors, fp32, rows picked through the live list) is read with loads in which 16 neighbouring
+//     lanes cover 256 contiguous bytes of a row, scaled, squared into the row's length, rounded to fp16 and
+//     passed through a small LDS tile that belongs to the wavefront alone, from which every lane takes its row.
+// There is no block barrier inside the K loop.  SPLITK: the 4 wavefronts each take every fourth stage of 64
+// channels and all 128 classes of the tile, and their partial tiles are added in LDS in wavefront order.
+// Otherwise (fewer than 4 stages) each takes all stages and 32 of the classes.
+constexpr int A_LD = 64 + 8;                             // halves per row of a wavefront's A tile (144 B: 16-byte reads without bank conflicts)
+
+template <int NJ>
+struct StageRegs {
+    f32x4 a[8];                                          // load u: row 4u + lane/16 of the tile, floats 4*(lane%16) .. +3 of the stage
+    u32x4 b[NJ][4];                                      // [class sub-tile][step]
+};
+
+template <int NJ>
+__device__ __forceinline__ void fetch_stage(StageRegs<NJ>& R, const float* sv, const int64_t (&a_off)[8], const _Float16* b_lane,
+                                            int64_t b_tile_stride, int stage) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) R.a[u] = *reinterpret_cast<const f32x4*>(sv + a_off[u] + 64 * stage);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            R.b[j][u] = *reinterpret_cast<const u32x4*>(b_lane + j * b_tile_stride + (int64_t)(4 * stage + u) * 512);
+}
+
+template <int NJ>
+__device__ __forceinline__ void multiply_stage(const StageRegs<NJ>& R, const float (&scale)[8], float (&ss)[8],
+                                               _Float16* a_tile, floatx16 (&acc)[NJ]) {
+    typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const f32x4 x = R.a[u] * scale[u];
+        ss[u] += (x.x * x.x + x.y * x.y) + (x.z * x.z + x.w * x.w);
+        const half4_t hv = {(_Float16)x.x, (_Float16)x.y, (_Float16)x.z, (_Float16)x.w};
+        *reinterpret_cast<half4_t*>(a_tile + (4 * u + (lane >> 4)) * A_LD + 4 * (lane & 15)) = hv;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        const half8_t av = *reinterpret_cast<const half8_t*>(a_tile + (lane & 31) * A_LD + 16 * ks + 8 * (lane >> 5));
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, __builtin_bit_cast(half8_t, R.b[j][ks]), acc[j], 0, 0, 0);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the tile is rewritten by the next stage
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <bool SPLITK>
+__global__ __launch_bounds__(256) void k_score_mfma(ScoreArgs a, const _Float16* __restrict__ chat, int Cp) {
+    constexpr int NJ = SPLITK ? 4 : 1;
+    constexpr int COPIES = SPLITK ? 4 : 1;
+    __shared__ __attribute__((aligned(16))) float red[COPIES * SC_M * SC_LD];
+    __shared__ __attribute__((aligned(16))) _Float16 a_tiles[4][SC_M * A_LD];
+    __shared__ float ss_part[4][SC_M];
+    __shared__ uint32_t row_bits[SC_M];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int m0 = blockIdx.y * SC_M, n0 = blockIdx.x * SC_N;
+    const int n_stage = Cp / 64;
+    const int j0 = SPLITK ? 0 : wave;                    // first 32-class sub-tile of this wavefront
+    const int s0 = SPLITK ? wave : 0, sstep = SPLITK ? 4 : 1;
+    const int my_n = s0 < n_stage ? (n_stage - s0 + sstep - 1) / sstep : 0;
+    auto stage_of = [&](int i) { return s0 + i * sstep; };
+
+    // The live count, the frame ids of the tile's rows and the centre operands do not depend on each other: all
+    // are requested before any is waited for.  The list has max_rows entries, every one a frame id of this or an
+    // earlier batch, so a row read for a slot past the live count is a real row (and is never used).
+    int n_live = a.counts->n_live;
+    int fid_a[8];                                        // frames of the rows this lane loads A for
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int slot = m0 + 4 * u + (lane >> 4);
+        fid_a[u] = a.frame_ids[slot < a.max_rows ? slot : a.max_rows - 1];
+    }
+    const int slot_e = m0 + (tid >> 3) < a.max_rows ? m0 + (tid >> 3) : a.max_rows - 1;
+    int fid_e = a.frame_ids[slot_e];                     // frame of this thread's epilogue row
+    const int64_t b_tile_stride = (int64_t)(Cp >> 4) * 512;              // halves between two 32-class tiles
+    const _Float16* b_lane = chat + (int64_t)((n0 >> 5) + j0) * b_tile_stride + lane * 8;
+    const u32x4 hotw = *reinterpret_cast<const u32x4*>(a.in_hot + n0 + (tid & 7) * 16);   // the mask is padded to whole tiles
+    StageRegs<NJ> R0, R1;
+    if (my_n > 0) {                                      // centre operands of the first stage: always in bounds
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                R0.b[j][u] = *reinterpret_cast<const u32x4*>(b_lane + j * b_tile_stride + (int64_t)(4 * stage_of(0) + u) * 512);
+    }
+    asm volatile("" : "+v"(fid_e), "+s"(n_live));
+    if (n_live > a.max_rows) n_live = a.max_rows;
+    if (m0 >= n_live) return;                            // uniform over the block
+
+    int64_t a_off[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a_off[u] = (int64_t)fid_a[u] * a.ldv + 4 * (lane & 15);
+    const uint32_t bits_e = row_max_bits(a.rowmax, a.rowmax_slots, fid_e);
+    f32x4 sa_old[4];
+    fetch_sa_old(a, fid_e, n0, sa_old);
+    if (my_n > 0) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) R0.a[u] = *reinterpret_cast<const f32x4*>(a.sv + a_off[u] + 64 * stage_of(0));
+    }
+    if ((tid & 7) == 0) row_bits[tid >> 3] = bits_e;
+    __syncthreads();
+    float scale[8], ss[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { scale[u] = row_scale_of(row_bits[4 * u + (lane >> 4)]).scale; ss[u] = 0.f; }
+
+    floatx16 acc[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    _Float16* a_tile = a_tiles[wave];
+    for (int i = 0; i < my_n; i += 2) {                  // two stages per trip so that the register sets are static:
+        if (i + 1 < my_n) fetch_stage<NJ>(R1, a.sv, a_off, b_lane, b_tile_stride, stage_of(i + 1));   // the next stage is
+        multiply_stage<NJ>(R0, scale, ss, a_tile, acc);                                                // in flight while this
+        if (i + 1 >= my_n) break;                                                                      // one is multiplied
+        if (i + 2 < my_n) fetch_stage<NJ>(R0, a.sv, a_off, b_lane, b_tile_stride, stage_of(i + 2));
+        multiply_stage<NJ>(R1, scale, ss, a_tile, acc);
+    }
+
+    // partial sums of squares (16 lanes share a row) and partial tiles to LDS
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        float t = ss[u];
+        t += __shfl_xor(t, 1, 64); t += __shfl_xor(t, 2, 64); t += __shfl_xor(t, 4, 64); t += __shfl_xor(t, 8, 64);
+        if ((lane & 15) == 0) ss_part[wave][4 * u + (lane >> 4)] = t;
+    }
+    float* my_red = red + (SPLITK ? wave * SC_M * SC_LD : 0);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int row = 8 * (e >> 2) + 4 * h + (e & 3);
+            my_red[row * SC_LD + (j0 + j) * 32 + r] = acc[j][e];
+        }
+    __syncthreads();
+    const int row_e = tid >> 3;
+    float ss_row = ss_part[0][row_e];
+    if (SPLITK) ss_row = ((ss_row + ss_part[1][row_e]) + ss_part[2][row_e]) + ss_part[3][row_e];
+    const RowScale re = row_scale_of(bits_e);            // whether the epilogue row is dead
+    score_epilogue(a, red, COPIES, ss_row, re.dead, nullptr, hotw, m0, n0, n_live, fid_e, sa_old);
+}
+
+void launch_score_mfma(const ScoreArgs& a, const _Float16* chat, int Cp, hipStream_t st) {
+    // centres are padded to kRowPad = 128 classes and Cp is a multiple of 64: a tile never reads outside them
+    dim3 grid((a.n + SC_N - 1) / SC_N, (a.max_rows + SC_M - 1) / SC_M);
+    if (Cp / 64 >= 4) hipLaunchKernelGGL((k_score_mfma<true>), grid, dim3(256), 0, st, a, chat, Cp);
+    else hipLaunchKernelGGL((k_score_mfma<false>), grid, dim3(256), 0, st, a, chat, Cp);
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32 scoring (fp32 feature maps, or on request): same tile, same epilogue; the contraction runs in fp32
+// vector arithmetic from LDS tiles of 16 channels.  Thread t owns frame t/8 and 16 consecutive classes, which
+// is also how the epilogue wants them, so the accumulators only pass through LDS to share its code.
+constexpr int FP_K = 16;
+
+__global__ __launch_bounds__(256) void k_score_fp32(ScoreArgs a, const float* __restrict__ centres,
+                                                    const float* __restrict__ cinv, int C) {
+    __shared__ __attribute__((aligned(16))) float red[SC_M * SC_LD];
+    __shared__ float As[FP_K][SC_M + 1];
+    __shared__ __attribute__((aligned(16))) float Bs[FP_K][SC_N + 4];
+    const int tid = threadIdx.x;
+    const int m0 = blockIdx.y * SC_M, n0 = blockIdx.x * SC_N;
+    const int row = tid >> 3, cg = tid & 7;
+    int n_live = a.counts->n_live;
+    const int slot_e = m0 + row < a.max_rows ? m0 + row : a.max_rows - 1;
+    int fid = a.frame_ids[slot_e];
+    asm volatile("" : "+v"(fid), "+s"(n_live));
+    if (n_live > a.max_rows) n_live = a.max_rows;
+    if (m0 >= n_live) return;                            // uniform over the block
+    const RowScale rs = row_scale_of(row_max_bits(a.rowmax, a.rowmax_slots, fid));
+    f32x4 sa_old[4];
+    fetch_sa_old(a, fid, n0, sa_old);
+    const u32x4 hotw = *reinterpret_cast<const u32x4*>(a.in_hot + n0 + cg * 16);          // the mask is padded to whole tiles
+    // loaders: A tile 32 frames x 16 channels, two per thread (the 8 threads of a frame load its 16 channels);
+    // B tile 128 classes x 16 channels, eight per thread
+    const float* a_ptr = a.sv + (int64_t)fid * a.ldv + cg * 2;          // padded with zeros up to ldv
+    const int b_cls = n0 + (tid >> 1), b_k = (tid & 1) * 8;
+    const float* b_ptr = b_cls < a.n ? centres + (int64_t)b_cls * C : nullptr;
+    float acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    float ss = 0.f;
+    for (int k0 = 0; k0 < C; k0 += FP_K) {
+        const float x0 = a_ptr[k0] * rs.scale, x1 = a_ptr[k0 + 1] * rs.scale;   // k0 + 1 < ldv: ldv is a multiple of 64
+        ss += x0 * x0 + x1 * x1;
+        As[cg * 2][row] = x0;
+        As[cg * 2 + 1][row] = x1;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int k = k0 + b_k + i;
+            Bs[b_k + i][tid >> 1] = (b_ptr && k < C) ? b_ptr[k] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < FP_K; ++kk) {
+            const float av = As[kk][row];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 b = *reinterpret_cast<const f32x4*>(&Bs[kk][cg * 16 + 4 * q]);
+                acc[4 * q] += av * b.x; acc[4 * q + 1] += av * b.y; acc[4 * q + 2] += av * b.z; acc[4 * q + 3] += av * b.w;
+            }
+        }
+        __syncthreads();
+    }
+    // sum of squares of the frame: its 8 loader threads are 8 neighbouring lanes
+    ss += __shfl_xor(ss, 1, 64);
+    ss += __shfl_xor(ss, 2, 64);
+    ss += __shfl_xor(ss, 4, 64);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) red[row * SC_LD + cg * 16 + i] = acc[i];
+    __syncthreads();
+    score_epilogue(a, red, 1, ss, rs.dead, cinv, hotw, m0, n0, n_live, fid, sa_old);
+}
+
+void launch_score_fp32(const ScoreArgs& a, const float* centres, const float* cinv, int C, hipStream_t st) {
+    dim3 grid((a.n + SC_N - 1) / SC_N, (a.max_rows + SC_M - 1) / SC_M);
+    hipLaunchKernelGGL(k_score_fp32, grid, dim3(256), 0, st, a, centres, cinv, C);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The decision as a kernel of its own (smtm_lookup); smtm_lookup_exit runs it at the head of the compaction.
+__global__ __launch_bounds__(256) void k_decide(DecideArgs g) {
+    int n_live = g.counts->n_live;
+    if (n_live > g.max_rows) n_live = g.max_rows;
+    for (int slot = blockIdx.x * 256 + threadIdx.x; slot < n_live; slot += gridDim.x * 256) decide_slot(g, slot);
+}
+
+void launch_decide(const DecideArgs& g, hipStream_t st) {
+    int grid = (g.max_rows + 255) / 256;
+    if (grid > 1024) grid = 1024;
+    hipLaunchKernelGGL(k_decide, dim3(grid), dim3(256), 0, st, g);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Single-layer separability (Eq. 2): sep = (s_H - s_SH) / s_SH over one exit point's similarities,
 // per tier.  A diagnostic, not on the decision path.  One wavefront per live slot.
 // +inf where s_SH <= 0 < s_H, -inf where s_H <= 0 or the tier has fewer than two entries.
@@ -552,16 +503,6 @@ void launch_separability(const float* sims, const Counts* counts, int max_rows, 
     int grid = (max_rows + 3) / 4;
     if (grid > 2048) grid = 2048;
     hipLaunchKernelGGL(k_separability, grid, dim3(256), 0, st, sims, counts, max_rows, n, in_hot, sep_out);
-}
-
-void launch_top2_decide(const float* SA, const int32_t* frame_ids, const Counts* counts, int max_rows,
-                        int n, const uint8_t* in_hot, int tiers, float tau, int32_t* decision,
-                        int32_t* label, float* top_val, int32_t* top_id, float* top_val_user,
-                        int32_t* top_id_user, hipStream_t st) {
-    int grid = (max_rows + 3) / 4;
-    if (grid > 2048) grid = 2048;
-    hipLaunchKernelGGL(k_top2_decide, grid, dim3(256), 0, st, SA, frame_ids, counts, max_rows, n, in_hot,
-                       tiers, tau, decision, label, top_val, top_id, top_val_user, top_id_user);
 }
 
 }  // namespace smtm

@@ -247,7 +247,7 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
             for (; i + 7 * G < cnt; i += 8 * G) {
                 float a[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) a[u] = sv[(int64_t)list[i + u * G] * C + c];
+                for (int u = 0; u < 8; ++u) a[u] = sv[(int64_t)list[i + u * G] * Cp + c];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) sum += a[u];
             }
@@ -256,7 +256,7 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     const int k = i + u * G;
-                    a[u] = sv[(int64_t)list[k < cnt ? k : i] * C + c];
+                    a[u] = sv[(int64_t)list[k < cnt ? k : i] * Cp + c];
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) sum += i + u * G < cnt ? a[u] : 0.f;
@@ -279,7 +279,7 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
                 for (; i + 32 <= cnt; i += 32) {
                     float a[32];
 #pragma unroll
-                    for (int u = 0; u < 32; ++u) a[u] = sv[(int64_t)list[i + u] * C + c];
+                    for (int u = 0; u < 32; ++u) a[u] = sv[(int64_t)list[i + u] * Cp + c];
 #pragma unroll
                     for (int u = 0; u < 32; ++u) sum += a[u];
                 }
@@ -288,19 +288,19 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
                 if (cnt - i > 8) {
                     float a[32];
 #pragma unroll
-                    for (int u = 0; u < 32; ++u) a[u] = sv[(int64_t)list[i + u < cnt ? i + u : i] * C + c];
+                    for (int u = 0; u < 32; ++u) a[u] = sv[(int64_t)list[i + u < cnt ? i + u : i] * Cp + c];
 #pragma unroll
                     for (int u = 0; u < 32; ++u) sum += i + u < cnt ? a[u] : 0.f;
                 } else if (cnt > i) {
                     float a[8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) a[u] = sv[(int64_t)list[i + u < cnt ? i + u : i] * C + c];
+                    for (int u = 0; u < 8; ++u) a[u] = sv[(int64_t)list[i + u < cnt ? i + u : i] * Cp + c];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) sum += i + u < cnt ? a[u] : 0.f;
                 }
             } else {                                     // more frames of one class than the list holds
                 for (int b = 0; b < batch; ++b)
-                    if (label[b] == j && usable_stop(stop_layer[b], res_layer[b], enc_upto) > l0) sum += sv[(int64_t)b * C + c];
+                    if (label[b] == j && usable_stop(stop_layer[b], res_layer[b], enc_upto) > l0) sum += sv[(int64_t)b * Cp + c];
             }
             const float x = (sc[c] * m_old + sum) / (m_old + (float)cnt);
             sc[c] = x;
@@ -318,11 +318,11 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
         const uint64_t mm = (uint64_t)tabs.mcount[l0][j] + (uint64_t)cnt;
         tabs.mcount[l0][j] = mm > 0xffffffffull ? 0xffffffffu : (uint32_t)mm;
     }
-    _Float16* ch = tabs.chat[l0] + (int64_t)j * Cp;
+    _Float16* ch = tabs.chat[l0];
     for (int c = tid; c < Cp; c += 256) {
         float x = 0.f;
         if (c < C && inv != 0.f) x = sc[c] * inv;        // sc[c] was written by this same thread
-        ch[c] = (_Float16)x;
+        ch[chat_index(j, c, Cp)] = (_Float16)x;
     }
 }
 

@@ -165,6 +165,33 @@ def test_resnet18_tau_sweep(tau):
     assert sum(rep.exit_hist) == w.batch
 
 
+# ------------------------------------------------------------------ wide vectors, extreme magnitudes
+
+@pytest.mark.parametrize("dtype,path", [("f32", SCORE_FP32), ("f32", SCORE_MFMA), ("f16", SCORE_MFMA), ("f16", SCORE_FP32)])
+def test_wide_vectors_of_any_magnitude(dtype, path):
+    # 4096 channels (more than one pass of any per-row loop), and frames whose feature maps are scaled by
+    # very different factors: the cosine does not depend on the scale, the arithmetic must not either
+    _say("wide vectors", dtype, path)
+    w = dataclasses.replace(configs.TINY, batch=45, dtype=dtype, exits=((4096, 1, 1), (200, 2, 2)), n_classes=21,
+                            hot=5, sigma=0.02, tau=0.5)
+    cents = streams.centroids(w); ls = streams.labels(w)
+    fm = streams.batch_feature_maps(w, cents, ls, 0, DEV)
+    if dtype == "f32":
+        factors = [1e-30, 1e-12, 1e-3, 1.0, 1e4, 1e12, 1e30]
+    else:
+        factors = [2e-3, 0.05, 1.0, 40.0, 3e4]
+    for i in range(w.batch):
+        for f in fm:
+            f[i] *= factors[i % len(factors)]
+    assert all(torch.isfinite(f).all() for f in fm)
+    ctx = P.make_ctx(w, cents, ls.initial_hot, tau=w.tau, score_path=path)
+    mem = P.make_oracle(w, cents, ls.initial_hot, tau=w.tau)
+    rep = P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w, path))
+    _say("  exits", rep.exit_hist, "max sim err (x tol)", rep.max_sim_err, "flips", rep.in_band_flips)
+    assert rep.exit_hist[1] + rep.exit_hist[2] > 0 and rep.max_sim_err <= 1.0
+    ctx.close()
+
+
 # ------------------------------------------------------------------ workloads 3 and 4 at full size
 
 def test_resnet50_full_size():
