@@ -138,7 +138,9 @@ int32_t smtm_set_tau(smtm_ctx* ctx, float tau);
 
 /* ---- one batch ----------------------------------------------------------------------------- */
 
-/* Starts a batch of `batch` frames: SA := 0 (Eq. 3), all frames live, per-frame results cleared. */
+/* Starts a batch of `batch` frames: SA := 0 (Eq. 3), all frames live, per-frame results cleared.
+ * The call itself enqueues nothing: the batch's first smtm_encode / smtm_stage carries the initialisation in its
+ * own kernel (one launch less per batch), and any other call that needs the batch's state enqueues it first. */
 int32_t smtm_begin_batch(smtm_ctx* ctx, int32_t batch, void* stream);
 
 /* 1. Encode (Sec. 4.1): semantic vector = mean over H x W of each channel, fp32 accumulation.

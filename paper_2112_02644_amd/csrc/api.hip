@@ -34,11 +34,14 @@ struct smtm_ctx {
     int32_t* ids_stage;                          // [hot_max] staging for smtm_hot_set
     // batch state
     float* SA;                                   // [max_batch, n] by original frame id (+ slack for unguarded tile loads)
-    float* sv[SMTM_MAX_EXITS];                   // [max_batch, Cp_l] by original frame id, columns >= C_l stay zero
+    float* sv[SMTM_MAX_EXITS];                   // [max_batch, Cp_l] by live slot at that exit point, columns >= C_l stay zero
+    int32_t* slot_of[SMTM_MAX_EXITS];            // [max_batch] live slot each frame had at that exit point
     uint32_t* rowmax;                            // [L, max_batch, kRowMaxSlots] partial maxima of |SV| per frame and exit point
     int enc_slots[SMTM_MAX_EXITS];               // slots per frame the last encode of each exit point filled
     float* part;                                 // [tiles, 6, max_batch] per-tile best / second best of the last lookup
     bool sa_fresh;                               // no lookup yet in this batch: the next one overwrites SA
+    bool begin_pending;                          // smtm_begin_batch has been called but its device work not enqueued yet:
+                                                 // the first encode of the batch does it, or flush_begin() before anything else
     int32_t* live[2];                            // ping-pong live lists
     int cur;
     int32_t* next_slots;                         // old slot of each survivor
@@ -203,6 +206,7 @@ int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
         CREATE_TRY(dev_alloc(ctx, &ctx->chat[l], (size_t)ctx->n_pad * ctx->Cp[l]));
         CREATE_TRY(dev_alloc(ctx, &ctx->mcount[l], (size_t)n));
         CREATE_TRY(dev_alloc(ctx, &ctx->sv[l], (size_t)B * ctx->Cp[l]));
+        CREATE_TRY(dev_alloc(ctx, &ctx->slot_of[l], (size_t)B));
     }
     CREATE_TRY(dev_alloc(ctx, &ctx->FT, (size_t)n));
     CREATE_TRY(dev_alloc(ctx, &ctx->TS, (size_t)n));
@@ -240,6 +244,7 @@ int32_t smtm_create(smtm_ctx** out, const smtm_config* cfg) {
         CREATE_TRY(hipMemset(ctx->cinv[l], 0, sizeof(float) * (size_t)n));
         CREATE_TRY(hipMemset(ctx->chat[l], 0, sizeof(_Float16) * (size_t)ctx->n_pad * ctx->Cp[l]));
         CREATE_TRY(hipMemset(ctx->sv[l], 0, sizeof(float) * (size_t)B * ctx->Cp[l]));
+        CREATE_TRY(hipMemset(ctx->slot_of[l], 0, sizeof(int32_t) * (size_t)B));
         launch_fill_u32(ctx->mcount[l], (uint32_t)cfg->init_count, n, nullptr);
     }
     launch_fill_u32(reinterpret_cast<uint32_t*>(ctx->all_exits), (uint32_t)L, B, nullptr);
@@ -377,15 +382,20 @@ int32_t smtm_begin_batch(smtm_ctx* ctx, int32_t batch, void* stream) {
     if (int32_t rc = check_ctx(ctx)) return rc;
     if (batch < 1 || batch > ctx->cfg.max_batch)
         return fail(ctx, SMTM_ERR_SHAPE, "batch %d outside 1..max_batch (%d)", batch, ctx->cfg.max_batch);
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    (void)stream;                                // nothing is enqueued here, see begin_pending
     ctx->cur = 0;
-    launch_begin_batch(batch, ctx->live[0], ctx->res_layer, ctx->res_label, ctx->res_tier, ctx->counts, st);
-    int32_t rc = check_launch(ctx, "smtm_begin_batch");
-    if (rc) return rc;
+    ctx->begin_pending = true;
     ctx->batch = batch;
     ctx->sa_fresh = true;
     for (int l = 0; l < SMTM_MAX_EXITS; ++l) ctx->stage_done[l] = 0;
     return SMTM_OK;
+}
+
+// The device side of smtm_begin_batch, for calls that are not an encode (an encode folds it into its kernel).
+static void flush_begin(smtm_ctx* ctx, hipStream_t st) {
+    if (!ctx->begin_pending) return;
+    launch_begin_batch(ctx->batch, ctx->live[0], ctx->res_layer, ctx->res_label, ctx->res_tier, ctx->counts, st);
+    ctx->begin_pending = false;
 }
 
 static int32_t check_encode_args(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t dtype, int32_t H, int32_t W) {
@@ -406,7 +416,15 @@ static int32_t encode_any(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int l = exit - 1;
     uint32_t* rowmax = ctx->rowmax + (size_t)l * ctx->cfg.max_batch * kRowMaxSlots;
-    const EncodeOut out = {ctx->sv[l], ctx->Cp[l], sv_out, rowmax};
+    EncodeOut out = {};
+    out.sv = ctx->sv[l]; out.ldv = ctx->Cp[l]; out.slot_of = ctx->slot_of[l]; out.sv_out = sv_out; out.rowmax = rowmax;
+    if (ctx->begin_pending) {
+        out.fresh = ctx->batch; out.live0 = ctx->live[0];
+        out.res_layer = ctx->res_layer; out.res_label = ctx->res_label; out.res_tier = ctx->res_tier;
+        out.counts_w = ctx->counts;
+        // the context's own list as row ids would be read before this kernel has written it: it is the identity
+        if (row_ids == ctx->live[0]) row_ids = nullptr;
+    }
     if (channels_last)
         launch_encode_nhwc(fmap, dtype, ctx->cfg.dims[l], H * W, row_ids, ctx->live[ctx->cur], ctx->counts,
                            ctx->batch, out, st, ctx->enc_kernel[l], sizeof(ctx->enc_kernel[l]), &ctx->enc_slots[l]);
@@ -415,6 +433,7 @@ static int32_t encode_any(smtm_ctx* ctx, int32_t exit, const void* fmap, int32_t
                       out, st, ctx->enc_kernel[l], sizeof(ctx->enc_kernel[l]), &ctx->enc_slots[l]);
     rc = check_launch(ctx, "smtm_encode");
     if (rc) return rc;
+    ctx->begin_pending = false;
     ctx->stage_done[l] = 1;
     ctx->enc_dtype[l] = dtype;
     return SMTM_OK;
@@ -599,6 +618,7 @@ int32_t smtm_batch_results(smtm_ctx* ctx, int32_t* exit_layer, int32_t* label, i
     if (int32_t rc = check_ctx(ctx)) return rc;
     if (ctx->batch == 0) return fail(ctx, SMTM_ERR_STATE, "smtm_begin_batch has not been called");
     hipStream_t st = static_cast<hipStream_t>(stream);
+    flush_begin(ctx, st);
     launch_copy3_i32(ctx->res_layer, exit_layer, ctx->res_label, label, ctx->res_tier, tier, ctx->batch, st);
     return check_launch(ctx, "smtm_batch_results");
 }
@@ -606,6 +626,7 @@ int32_t smtm_batch_results(smtm_ctx* ctx, int32_t* exit_layer, int32_t* label, i
 int32_t smtm_read_counts(smtm_ctx* ctx, int32_t* n_live_host, int32_t* n_exit_host, void* stream) {
     if (int32_t rc = check_ctx(ctx)) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    flush_begin(ctx, st);
     Counts c;
     HIP_TRY(ctx, hipMemcpyAsync(&c, ctx->counts, sizeof(Counts), hipMemcpyDeviceToHost, st));
     HIP_TRY(ctx, hipStreamSynchronize(st));
@@ -618,6 +639,7 @@ int32_t smtm_read_stats(smtm_ctx* ctx, int32_t* stats_host, void* stream) {
     if (int32_t rc = check_ctx(ctx)) return rc;
     if (!stats_host) return fail(ctx, SMTM_ERR_INVALID_ARG, "stats_host is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
+    flush_begin(ctx, st);
     Counts c;
     HIP_TRY(ctx, hipMemcpyAsync(&c, ctx->counts, sizeof(Counts), hipMemcpyDeviceToHost, st));
     HIP_TRY(ctx, hipStreamSynchronize(st));
@@ -635,6 +657,7 @@ static CentreTables centre_tables(const smtm_ctx* ctx) {
         tabs.cinv[l] = on ? ctx->cinv[l] : nullptr;
         tabs.chat[l] = on ? ctx->chat[l] : nullptr;
         tabs.sv[l] = on ? ctx->sv[l] : nullptr;
+        tabs.slot_of[l] = on ? ctx->slot_of[l] : nullptr;
         tabs.C[l] = on ? ctx->cfg.dims[l] : 0;
         tabs.Cp[l] = on ? ctx->Cp[l] : 0;
     }
@@ -683,6 +706,7 @@ static int32_t cache_update_with(smtm_ctx* ctx, const int32_t* label, const int3
     if (!label) { label = ctx->res_label; stop_layer = ctx->res_layer; }     // the batch's own exits
     if (batch != ctx->batch) return fail(ctx, SMTM_ERR_SHAPE, "batch %d differs from the batch begun (%d)", batch, ctx->batch);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    flush_begin(ctx, st);
     const smtm_config& c = ctx->cfg;
     const int n = c.n_classes;
     launch_tables_update(label, batch, n, (uint32_t)c.window, ctx->FT, ctx->TS, us.cls_cnt, us.cls_last,

@@ -51,9 +51,11 @@ __device__ __forceinline__ void compact_block(const CompactArgs& a, const Decide
     // max_rows entries.
     int n_live = a.counts->n_live;
     int d0 = 0, frame0 = 0, lab0 = -1;
+    SlotTop2 m0 = {};
     if (tid < a.max_rows) {
         frame0 = a.frame_ids[tid];
         if (!g) { d0 = a.decision[tid]; lab0 = a.label[tid]; }
+        else m0 = merge_slot(*g, tid);                   // loads only, valid for any slot of the batch
     }
     asm volatile("" : "+v"(d0), "+v"(frame0), "+v"(lab0), "+s"(n_live));   // issued before any is waited for
     if (tid == 0) { base_exit = 0; base_t1 = 0; }
@@ -68,7 +70,10 @@ __device__ __forceinline__ void compact_block(const CompactArgs& a, const Decide
                 frame = a.frame_ids[slot];
                 if (!g) { d = a.decision[slot]; lab = a.label[slot]; }
             }
-            if (g) { const SlotDecision sd = decide_slot(*g, slot); d = sd.d; lab = sd.label; }
+            if (g) {
+                const SlotDecision sd = c0 == 0 ? finish_slot(*g, slot, m0) : decide_slot(*g, slot);
+                d = sd.d; lab = sd.label;
+            }
         }
         const bool ex = valid && d != 0;
         const unsigned long long m_ex = __ballot(ex);

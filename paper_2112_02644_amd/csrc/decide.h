@@ -47,9 +47,15 @@ __device__ __forceinline__ bool exit_rule(float h, float sh, float tau) {
 
 // ---------------------------------------------------------------------------------------------
 // Decision of one live slot from its per-tile partial results (Sec. 5 Step 3, Sec. 6 tiers, Eq. 4).
-__device__ __forceinline__ SlotDecision decide_slot(const DecideArgs& g, int slot) {
+struct SlotTop2 {
+    Top2 hot, all;
+};
+
+// Loads only: the slot's per-tile results merged in tile order.  Safe for any slot below part_stride (the
+// buffer is allocated in full), so it can be issued before the live count is known.
+__device__ __forceinline__ SlotTop2 merge_slot(const DecideArgs& g, int slot) {
     const float ninf = -__builtin_inff();
-    Top2 hot = {ninf, -1, ninf}, all = {ninf, -1, ninf};
+    SlotTop2 m = {{ninf, -1, ninf}, {ninf, -1, ninf}};
     const float* p = g.part + slot;
     const int64_t ps = g.part_stride;
     int t = 0;
@@ -61,17 +67,25 @@ __device__ __forceinline__ SlotDecision decide_slot(const DecideArgs& g, int slo
             for (int k = 0; k < SC_FIELDS; ++k) f[u][k] = p[((int64_t)(t + u) * SC_FIELDS + k) * ps];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            top2_merge(hot, f[u][0], __builtin_bit_cast(int, f[u][1]), f[u][2]);
-            top2_merge(all, f[u][3], __builtin_bit_cast(int, f[u][4]), f[u][5]);
+            top2_merge(m.hot, f[u][0], __builtin_bit_cast(int, f[u][1]), f[u][2]);
+            top2_merge(m.all, f[u][3], __builtin_bit_cast(int, f[u][4]), f[u][5]);
         }
     }
     for (; t < g.tiles; ++t) {
         float f[SC_FIELDS];
 #pragma unroll
         for (int k = 0; k < SC_FIELDS; ++k) f[k] = p[((int64_t)t * SC_FIELDS + k) * ps];
-        top2_merge(hot, f[0], __builtin_bit_cast(int, f[1]), f[2]);
-        top2_merge(all, f[3], __builtin_bit_cast(int, f[4]), f[5]);
+        top2_merge(m.hot, f[0], __builtin_bit_cast(int, f[1]), f[2]);
+        top2_merge(m.all, f[3], __builtin_bit_cast(int, f[4]), f[5]);
     }
+    return m;
+}
+
+// The exit rule on the merged values, and everything a live slot writes.
+__device__ __forceinline__ SlotDecision finish_slot(const DecideArgs& g, int slot, SlotTop2 m) {
+    const float ninf = -__builtin_inff();
+    Top2& hot = m.hot;
+    Top2& all = m.all;
     SlotDecision o;
     o.d = 0; o.label = -1;
     if (exit_rule(hot.v1, hot.v2, g.tau)) { o.d = 1; o.label = hot.id1; }
@@ -88,6 +102,10 @@ __device__ __forceinline__ SlotDecision decide_slot(const DecideArgs& g, int slo
     g.decision[slot] = o.d;
     g.label[slot] = o.label;
     return o;
+}
+
+__device__ __forceinline__ SlotDecision decide_slot(const DecideArgs& g, int slot) {
+    return finish_slot(g, slot, merge_slot(g, slot));
 }
 
 }  // namespace smtm

@@ -37,6 +37,9 @@ __device__ __forceinline__ float sum_halves(uint32_t w) {
 // measured 6 % faster than longer walks or walks that jump through the frame), a worker (wavefront or block) takes a whole bin, keeps the largest |SV| it produced there as the bit pattern of a non-negative float
 // (which orders like the value; a NaN sorts above infinity) and stores it in the frame's slot of that bin.
 // Every slot of a live frame is rewritten by every encode, so nothing has to be cleared.
+// Semantic vectors and these maxima are stored by live slot (dense, in the order the scoring kernel walks them);
+// the worker of a frame's first bin also records the frame's slot, through which the centre update finds the
+// vector of a frame later.
 __device__ __forceinline__ uint32_t abs_bits(float m) { return __builtin_bit_cast(uint32_t, m) & 0x7fffffffu; }
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t bits) {
@@ -45,6 +48,22 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t bits) {
         bits = other > bits ? other : bits;
     }
     return bits;
+}
+
+// Live count of this launch; on the first encode of a batch also the batch's initial state (see EncodeOut).
+__device__ __forceinline__ int live_count(const EncodeOut& o, const Counts* counts, int max_rows) {
+    if (o.fresh) {
+        const int tid = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
+        for (int i = tid; i < o.fresh; i += stride) {
+            o.live0[i] = i;
+            o.res_layer[i] = 0; o.res_label[i] = -1; o.res_tier[i] = 0;
+        }
+        if (tid == 0) { o.counts_w->n_live = o.fresh; o.counts_w->n_exit = 0; }
+        if (tid < SMTM_MAX_EXITS * 4) o.counts_w->stats[tid >> 2][tid & 3] = 0;
+        return o.fresh;
+    }
+    const int n = counts->n_live;
+    return n > max_rows ? max_rows : n;
 }
 
 // first task of bin b when tpf tasks are split into nslots bins (nslots <= tpf, so no bin is empty)
@@ -103,15 +122,14 @@ __global__ __launch_bounds__(256) void k_encode_direct(
     const int cpw = 64 >> g_log2;                       // channels per wavefront task
     const int tpf = (C + cpw - 1) / cpw;                // tasks per frame
     const int nv = (int)((int64_t)HW * sizeof(T) / VB); // chunks per channel
-    int n_live = counts->n_live;
-    if (n_live > max_rows) n_live = max_rows;
+    const int n_live = live_count(o, counts, max_rows);
     const int64_t total = (int64_t)n_live * nslots;     // bins
 
     for (int64_t bb = wave; bb < total; bb += n_waves) {
         const int slot = (int)(bb / nslots);
         const int bin = (int)(bb - (int64_t)slot * nslots);
         const int64_t row = row_ids ? row_ids[slot] : slot;
-        const int frame = frame_ids[slot];
+        const int frame = o.fresh ? slot : frame_ids[slot];
         uint32_t mx = 0u;
         const int t_hi = bin_lo(bin + 1, tpf, nslots);
         for (int task = bin_lo(bin, tpf, nslots); task < t_hi; ++task) {
@@ -142,14 +160,17 @@ __global__ __launch_bounds__(256) void k_encode_direct(
             for (int off = g >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
             if (sub == 0 && c < C) {
                 const float m = acc / (float)HW;
-                o.sv[(int64_t)frame * o.ldv + c] = m;
+                o.sv[(int64_t)slot * o.ldv + c] = m;
                 if (o.sv_out) o.sv_out[(int64_t)slot * C + c] = m;
                 const uint32_t b = abs_bits(m);
                 mx = b > mx ? b : mx;
             }
         }
         mx = wave_max_u32(mx);
-        if (lane == 0) o.rowmax[(int64_t)frame * kRowMaxSlots + bin] = mx;
+        if (lane == 0) {
+            o.rowmax[(int64_t)slot * kRowMaxSlots + bin] = mx;
+            if (bin == 0) o.slot_of[frame] = slot;
+        }
     }
 }
 
@@ -213,8 +234,7 @@ __global__ __launch_bounds__(256) void k_encode_lds(
     u32x4* my16 = lds16 + wave * (tile_bytes >> 4);
     T* myT = reinterpret_cast<T*>(my16);
     const int gpf = (C + 63) >> 6;                       // tasks (64-channel groups) per frame
-    int n_live = counts->n_live;
-    if (n_live > max_rows) n_live = max_rows;
+    const int n_live = live_count(o, counts, max_rows);
     const int64_t total = (int64_t)n_live * nslots;      // bins
     const int64_t n_waves = (int64_t)gridDim.x * 4;
 
@@ -228,7 +248,7 @@ __global__ __launch_bounds__(256) void k_encode_lds(
         k.bin = (int)(bb - (int64_t)k.slot * nslots);
         k.cg = bin_lo(k.bin, gpf, nslots);
         k.hi = bin_lo(k.bin + 1, gpf, nslots);
-        k.frame = frame_ids[k.slot];
+        k.frame = o.fresh ? k.slot : frame_ids[k.slot];
     };
     auto fetch = [&](Task& k, u32x4 (&v)[UNR], T& tail) {
         k.nch = C - k.cg * 64;
@@ -274,14 +294,17 @@ __global__ __launch_bounds__(256) void k_encode_lds(
         if (lane < cur.nch) {
             const float m = lds_channel_sum<T>(myT, lane * HW, HW) / (float)HW;
             const int c = cur.cg * 64 + lane;
-            o.sv[(int64_t)cur.frame * o.ldv + c] = m;
+            o.sv[(int64_t)cur.slot * o.ldv + c] = m;
             if (o.sv_out) o.sv_out[(int64_t)cur.slot * C + c] = m;
             const uint32_t b = abs_bits(m);
             mx = b > mx ? b : mx;
         }
         if (last_of_bin) {
             mx = wave_max_u32(mx);
-            if (lane == 0) o.rowmax[(int64_t)cur.frame * kRowMaxSlots + cur.bin] = mx;
+            if (lane == 0) {
+                o.rowmax[(int64_t)cur.slot * kRowMaxSlots + cur.bin] = mx;
+                if (cur.bin == 0) o.slot_of[cur.frame] = cur.slot;
+            }
             mx = 0u;
         }
         wave_lds_order();
@@ -336,8 +359,7 @@ __global__ __launch_bounds__(256) void k_encode_flat(
     const int tpf = (C + cps - 1) / cps;                 // tasks (runs of cps channels) per frame
     const int lpc = 1 << lpc_log2;                       // lanes that share a channel's units (cps * lpc <= 64)
     const int ch = lane >> lpc_log2, part = lane & (lpc - 1);
-    int n_live = counts->n_live;
-    if (n_live > max_rows) n_live = max_rows;
+    const int n_live = live_count(o, counts, max_rows);
     const int64_t total = (int64_t)n_live * nslots;      // bins
     const int64_t n_waves = (int64_t)gridDim.x * 4;
 
@@ -347,7 +369,7 @@ __global__ __launch_bounds__(256) void k_encode_flat(
         k.bin = (int)(bb - (int64_t)k.slot * nslots);
         k.task = bin_lo(k.bin, tpf, nslots);
         k.hi = bin_lo(k.bin + 1, tpf, nslots);
-        k.frame = frame_ids[k.slot];
+        k.frame = o.fresh ? k.slot : frame_ids[k.slot];
     };
     auto fetch = [&](Task& k, u32x4 (&v)[UNR]) {
         k.nch = C - k.task * cps;
@@ -394,14 +416,17 @@ __global__ __launch_bounds__(256) void k_encode_flat(
         if (part == 0 && ch < cur.nch) {
             const float m = acc / (float)HW;
             const int c = cur.task * cps + ch;
-            o.sv[(int64_t)cur.frame * o.ldv + c] = m;
+            o.sv[(int64_t)cur.slot * o.ldv + c] = m;
             if (o.sv_out) o.sv_out[(int64_t)cur.slot * C + c] = m;
             const uint32_t b = abs_bits(m);
             mx = b > mx ? b : mx;
         }
         if (last_of_bin) {
             mx = wave_max_u32(mx);
-            if (lane == 0) o.rowmax[(int64_t)cur.frame * kRowMaxSlots + cur.bin] = mx;
+            if (lane == 0) {
+                o.rowmax[(int64_t)cur.slot * kRowMaxSlots + cur.bin] = mx;
+                if (cur.bin == 0) o.slot_of[cur.frame] = cur.slot;
+            }
             mx = 0u;
         }
         wave_lds_order();
@@ -424,13 +449,12 @@ __global__ __launch_bounds__(1024) void k_encode_nhwc(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int cpr = C / E;                               // chunks per position row (C is a multiple of E here)
     const int n_slabs = (cpr + 63) >> 6;                 // tasks per frame
-    int n_live = counts->n_live;
-    if (n_live > max_rows) n_live = max_rows;
+    const int n_live = live_count(o, counts, max_rows);
     const int64_t total = (int64_t)n_live * nslots;      // bins
     for (int64_t bb = blockIdx.x; bb < total; bb += gridDim.x) {     // uniform over the block
       const int slot = (int)(bb / nslots);
       const int bin = (int)(bb - (int64_t)slot * nslots);
-      const int frame = frame_ids[slot];
+      const int frame = o.fresh ? slot : frame_ids[slot];
       uint32_t mx = 0u;
       const int s_hi = bin_lo(bin + 1, n_slabs, nslots);
       for (int slab = bin_lo(bin, n_slabs, nslots); slab < s_hi; ++slab) {
@@ -484,7 +508,7 @@ __global__ __launch_bounds__(1024) void k_encode_nhwc(
                 for (int j = 0; j < ppl; ++j) sum += part[(w * 64 + j * sw + kk) * E + e];
             const float m = sum / (float)HW;
             const int c = slab * 64 * E + q;
-            o.sv[(int64_t)frame * o.ldv + c] = m;
+            o.sv[(int64_t)slot * o.ldv + c] = m;
             if (o.sv_out) o.sv_out[(int64_t)slot * C + c] = m;
             const uint32_t b = abs_bits(m);
             mx = b > mx ? b : mx;
@@ -498,7 +522,8 @@ __global__ __launch_bounds__(1024) void k_encode_nhwc(
       if (threadIdx.x == 0) {
           uint32_t m = 0u;
           for (int w = 0; w < nw; ++w) m = wmax[w] > m ? wmax[w] : m;
-          o.rowmax[(int64_t)frame * kRowMaxSlots + bin] = m;
+          o.rowmax[(int64_t)slot * kRowMaxSlots + bin] = m;
+          if (bin == 0) o.slot_of[frame] = slot;
       }
       __syncthreads();
     }
@@ -512,14 +537,13 @@ __global__ __launch_bounds__(256) void k_encode_nhwc_scalar(
     const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows,
     EncodeOut o, int C, int HW, int nslots) {
     __shared__ uint32_t wmax[4];
-    int n_live = counts->n_live;
-    if (n_live > max_rows) n_live = max_rows;
+    const int n_live = live_count(o, counts, max_rows);
     const int cb = (C + 255) / 256;                      // tasks (256-channel blocks) per frame
     const int64_t total = (int64_t)n_live * nslots;      // bins
     for (int64_t bb = blockIdx.x; bb < total; bb += gridDim.x) {     // uniform over the block
         const int slot = (int)(bb / nslots);
         const int bin = (int)(bb - (int64_t)slot * nslots);
-        const int frame = frame_ids[slot];
+        const int frame = o.fresh ? slot : frame_ids[slot];
         const int64_t row = row_ids ? row_ids[slot] : slot;
         uint32_t mx = 0u;
         const int t_hi = bin_lo(bin + 1, cb, nslots);
@@ -535,7 +559,7 @@ __global__ __launch_bounds__(256) void k_encode_nhwc_scalar(
                 }
                 for (; i < HW; ++i) a0 += (float)p[(int64_t)i * C];
                 const float m = ((a0 + a1) + (a2 + a3)) / (float)HW;
-                o.sv[(int64_t)frame * o.ldv + c] = m;
+                o.sv[(int64_t)slot * o.ldv + c] = m;
                 if (o.sv_out) o.sv_out[(int64_t)slot * C + c] = m;
                 const uint32_t b = abs_bits(m);
                 mx = b > mx ? b : mx;
@@ -547,7 +571,8 @@ __global__ __launch_bounds__(256) void k_encode_nhwc_scalar(
         if (threadIdx.x == 0) {
             uint32_t m = wmax[0];
             for (int w = 1; w < 4; ++w) m = wmax[w] > m ? wmax[w] : m;
-            o.rowmax[(int64_t)frame * kRowMaxSlots + bin] = m;
+            o.rowmax[(int64_t)slot * kRowMaxSlots + bin] = m;
+            if (bin == 0) o.slot_of[frame] = slot;
         }
         __syncthreads();
     }
@@ -655,13 +680,9 @@ const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int3
         const int gpf = (C + 63) / 64;
         const int nslots = slots_for(gpf);
         *slots = nslots;
-        int grid = encode_grid((int64_t)max_rows * nslots, 4);
-        // as many blocks as stay resident at once (160 KB of LDS per CU, 8 blocks of 256 threads at most):
-        // each wavefront then walks several tasks and overlaps one task's sums with the next one's loads
-        int per_cu = (int)((160 * 1024) / ((size_t)tile_bytes * 4));
-        if (per_cu > 8) per_cu = 8;
-        if (per_cu < 1) per_cu = 1;
-        if (grid > 256 * per_cu) grid = 256 * per_cu;
+        // one block per four bins (measured against a grid cut down to what stays resident: 38 against 41 us for
+        // 1024 frames of 2048 x 7 x 7; the dispatcher evens out the tail better than long walks per wavefront)
+        const int grid = encode_grid((int64_t)max_rows * nslots, 4);
         const size_t lds = (size_t)tile_bytes * 4;
         // one round of UNR 16-byte loads per lane has to cover a task (64 channels): 8 up to 128-byte channels, else 16
 #define SMTM_LAUNCH_LDS(T, UNR)                                                                              \

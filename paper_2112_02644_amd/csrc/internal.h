@@ -53,10 +53,18 @@ __host__ __device__ static inline int64_t chat_index(int j, int c, int Cp) {
 // and writes the name of the kernel instance it launched to `name` and the number of partial-maximum slots it fills
 // per frame to `slots`.
 struct EncodeOut {
-    float* sv;                            // [frames, ldv] by original frame id
+    float* sv;                            // [max_rows, ldv] by live slot
     int ldv;
+    int32_t* slot_of;                     // [frames] live slot of each frame at this exit point
     float* sv_out;                        // [max_rows, C] by slot, or NULL
-    uint32_t* rowmax;                     // [frames, kRowMaxSlots] largest |SV| (bit pattern) per bin of the frame's channel groups
+    // Start of a batch folded into its first encode (saves a launch): fresh = batch size (0 = not the first encode).
+    // The kernel then takes every frame as live in identity order instead of reading the count and the list, and
+    // its threads also write what k_begin_batch would have written (list, per-frame results, counters).
+    int fresh;
+    int32_t* live0;                       // [batch] live list to initialise
+    int32_t *res_layer, *res_label, *res_tier;
+    Counts* counts_w;
+    uint32_t* rowmax;                     // [max_rows, kRowMaxSlots] by live slot: largest |SV| (bit pattern) per bin of the frame's channel groups
 };
 const char* launch_encode(const void* fmap, int dtype, int C, int HW, const int32_t* row_ids,
                           const int32_t* frame_ids, const Counts* counts, int max_rows,
@@ -75,9 +83,9 @@ constexpr int kScoreTileRows = 32;        // live frames per scoring tile
 constexpr int kScoreTileCols = 128;       // classes per scoring tile (= kRowPad)
 
 struct ScoreArgs {
-    const float* sv;                      // [frames, ldv] fp32 semantic vectors by original frame id
+    const float* sv;                      // [max_rows, ldv] fp32 semantic vectors by live slot
     int ldv;                              // row stride of sv (channels rounded up to kKPad, zero padded)
-    const uint32_t* rowmax;               // [frames, kRowMaxSlots] partial maxima of |SV| (bit patterns) at this exit point
+    const uint32_t* rowmax;               // [max_rows, kRowMaxSlots] by live slot: partial maxima of |SV| (bit patterns)
     int rowmax_slots;                     // how many of a frame's slots the encode kernel filled
     const int32_t* frame_ids;             // [max_rows] live list
     const Counts* counts;
@@ -137,7 +145,8 @@ struct CentreTables {                     // per exit point, passed by value to 
     uint32_t* mcount[SMTM_MAX_EXITS];
     float* cinv[SMTM_MAX_EXITS];
     _Float16* chat[SMTM_MAX_EXITS];
-    const float* sv[SMTM_MAX_EXITS];      // [batch, Cp] saved semantic vectors by original frame id
+    const float* sv[SMTM_MAX_EXITS];      // [batch, Cp] saved semantic vectors by the live slot the frame had at that exit point
+    const int32_t* slot_of[SMTM_MAX_EXITS];   // [batch] that slot, by original frame id (valid for frames live at the exit point)
     int C[SMTM_MAX_EXITS];
     int Cp[SMTM_MAX_EXITS];               // channels rounded up to kKPad: row stride of chat and of sv
     const int32_t* res_layer;             // [batch] exit point at which the library released the frame, 0 = not released

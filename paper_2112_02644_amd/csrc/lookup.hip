@@ -88,11 +88,12 @@ __device__ __forceinline__ RowScale row_scale_of(uint32_t max_bits) {
     return r;
 }
 
-// Largest |SV| of the frame of an epilogue row: thread (row = tid/8, k = tid%8) looks at the frame's slots
-// 8k .. 8k+7 (the encode kernel filled the first `slots` of the kRowMaxSlots = 64) and the 8 threads of the row combine.
-__device__ __forceinline__ uint32_t row_max_bits(const uint32_t* __restrict__ rowmax, int slots, int fid) {
+// Largest |SV| of the frame in live slot `slot` (an epilogue row): thread (row = tid/8, k = tid%8) looks at the
+// entries 8k .. 8k+7 of the slot (the encode kernel filled the first `slots` of the kRowMaxSlots = 64) and the 8
+// threads of the row combine.  Any slot below max_rows is readable.
+__device__ __forceinline__ uint32_t row_max_bits(const uint32_t* __restrict__ rowmax, int slots, int slot) {
     const int k = threadIdx.x & 7;
-    const u32x4* p = reinterpret_cast<const u32x4*>(rowmax + (int64_t)fid * kRowMaxSlots + 8 * k);
+    const u32x4* p = reinterpret_cast<const u32x4*>(rowmax + (int64_t)slot * kRowMaxSlots + 8 * k);
     const u32x4 lo = p[0], hi = p[1];
     uint32_t a = 0u;
 #pragma unroll
@@ -287,43 +288,31 @@ __global__ __launch_bounds__(256) void k_score_mfma(ScoreArgs a, const _Float16*
     const int my_n = s0 < n_stage ? (n_stage - s0 + sstep - 1) / sstep : 0;
     auto stage_of = [&](int i) { return s0 + i * sstep; };
 
-    // The live count, the frame ids of the tile's rows and the centre operands do not depend on each other: all
-    // are requested before any is waited for.  The list has max_rows entries, every one a frame id of this or an
-    // earlier batch, so a row read for a slot past the live count is a real row (and is never used).
+    // Semantic vectors and their maxima are stored by live slot, so everything the contraction needs is addressed
+    // without the live list: live count, vectors, maxima, centre operands, fast-memory mask and the frame id of
+    // the epilogue row (for SA, which is kept by frame) are all requested before any of them is waited for.  Rows
+    // of slots past the live count are readable (the buffers hold max_rows rows) and never used.
     int n_live = a.counts->n_live;
-    int fid_a[8];                                        // frames of the rows this lane loads A for
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const int slot = m0 + 4 * u + (lane >> 4);
-        fid_a[u] = a.frame_ids[slot < a.max_rows ? slot : a.max_rows - 1];
-    }
     const int slot_e = m0 + (tid >> 3) < a.max_rows ? m0 + (tid >> 3) : a.max_rows - 1;
     int fid_e = a.frame_ids[slot_e];                     // frame of this thread's epilogue row
     const int64_t b_tile_stride = (int64_t)(Cp >> 4) * 512;              // halves between two 32-class tiles
     const _Float16* b_lane = chat + (int64_t)((n0 >> 5) + j0) * b_tile_stride + lane * 8;
     const u32x4 hotw = *reinterpret_cast<const u32x4*>(a.in_hot + n0 + (tid & 7) * 16);   // the mask is padded to whole tiles
-    StageRegs<NJ> R0, R1;
-    if (my_n > 0) {                                      // centre operands of the first stage: always in bounds
+    int64_t a_off[8];
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                R0.b[j][u] = *reinterpret_cast<const u32x4*>(b_lane + j * b_tile_stride + (int64_t)(4 * stage_of(0) + u) * 512);
+    for (int u = 0; u < 8; ++u) {
+        const int slot = m0 + 4 * u + (lane >> 4);
+        a_off[u] = (int64_t)(slot < a.max_rows ? slot : a.max_rows - 1) * a.ldv + 4 * (lane & 15);
     }
+    const uint32_t bits_e = row_max_bits(a.rowmax, a.rowmax_slots, slot_e);
+    StageRegs<NJ> R0, R1;
+    if (my_n > 0) fetch_stage<NJ>(R0, a.sv, a_off, b_lane, b_tile_stride, stage_of(0));
     asm volatile("" : "+v"(fid_e), "+s"(n_live));
     if (n_live > a.max_rows) n_live = a.max_rows;
     if (m0 >= n_live) return;                            // uniform over the block
 
-    int64_t a_off[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) a_off[u] = (int64_t)fid_a[u] * a.ldv + 4 * (lane & 15);
-    const uint32_t bits_e = row_max_bits(a.rowmax, a.rowmax_slots, fid_e);
     f32x4 sa_old[4];
     fetch_sa_old(a, fid_e, n0, sa_old);
-    if (my_n > 0) {
-#pragma unroll
-        for (int u = 0; u < 8; ++u) R0.a[u] = *reinterpret_cast<const f32x4*>(a.sv + a_off[u] + 64 * stage_of(0));
-    }
     if ((tid & 7) == 0) row_bits[tid >> 3] = bits_e;
     __syncthreads();
     float scale[8], ss[8];
@@ -394,13 +383,13 @@ __global__ __launch_bounds__(256) void k_score_fp32(ScoreArgs a, const float* __
     asm volatile("" : "+v"(fid), "+s"(n_live));
     if (n_live > a.max_rows) n_live = a.max_rows;
     if (m0 >= n_live) return;                            // uniform over the block
-    const RowScale rs = row_scale_of(row_max_bits(a.rowmax, a.rowmax_slots, fid));
+    const RowScale rs = row_scale_of(row_max_bits(a.rowmax, a.rowmax_slots, slot_e));
     f32x4 sa_old[4];
     fetch_sa_old(a, fid, n0, sa_old);
     const u32x4 hotw = *reinterpret_cast<const u32x4*>(a.in_hot + n0 + cg * 16);          // the mask is padded to whole tiles
     // loaders: A tile 32 frames x 16 channels, two per thread (the 8 threads of a frame load its 16 channels);
     // B tile 128 classes x 16 channels, eight per thread
-    const float* a_ptr = a.sv + (int64_t)fid * a.ldv + cg * 2;          // padded with zeros up to ldv
+    const float* a_ptr = a.sv + (int64_t)slot_e * a.ldv + cg * 2;       // by live slot; padded with zeros up to ldv
     const int b_cls = n0 + (tid >> 1), b_k = (tid & 1) * 8;
     const float* b_ptr = b_cls < a.n ? centres + (int64_t)b_cls * C : nullptr;
     float acc[16];

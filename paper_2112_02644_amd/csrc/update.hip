@@ -179,6 +179,7 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
     const int C = tabs.C[l0], Cp = tabs.Cp[l0];
     float* sc = tabs.centres[l0] + (int64_t)j * C;
     const float* sv = tabs.sv[l0];
+    const int32_t* __restrict__ slot_of = tabs.slot_of[l0];
 
     // frames of this class that reached this exit point, ascending.  A thread looks at four consecutive
     // frames per pass (one 16-byte load from each array when they are aligned), so a batch of 1024 is one
@@ -218,7 +219,7 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
         for (int k = 0; k < 4; ++k) {
             if (hit[k]) {
                 const int pos = cnt + off + pre + own;
-                if (pos < kListCap) list[pos] = b + k;
+                if (pos < kListCap) list[pos] = slot_of[b + k];      // where the frame's vector of this exit point is
                 ++own;
             }
         }
@@ -300,7 +301,7 @@ __device__ __forceinline__ void centres_block(const CentreTables& tabs, const in
                 }
             } else {                                     // more frames of one class than the list holds
                 for (int b = 0; b < batch; ++b)
-                    if (label[b] == j && usable_stop(stop_layer[b], res_layer[b], enc_upto) > l0) sum += sv[(int64_t)b * Cp + c];
+                    if (label[b] == j && usable_stop(stop_layer[b], res_layer[b], enc_upto) > l0) sum += sv[(int64_t)slot_of[b] * Cp + c];
             }
             const float x = (sc[c] * m_old + sum) / (m_old + (float)cnt);
             sc[c] = x;
