@@ -124,6 +124,23 @@ def make_oracle(w: Workload, cents, hot_ids, *, tau=None, tiers=None, forgetting
                     hot_max=w.hot_max or len(hot_ids), init_count=w.init_count, forgetting=forgetting)
 
 
+_pinned = {}
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> numpy through a pinned staging buffer kept per shape (several times faster than a
+    pageable copy for the GB-sized feature maps).  The array is a view of the buffer: use it before the next
+    call with the same shape."""
+    key = (tuple(t.shape), t.dtype)
+    buf = _pinned.get(key)
+    if buf is None:
+        if len(_pinned) > 24:
+            _pinned.clear()
+        buf = _pinned[key] = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+    buf.copy_(t)
+    return buf.numpy()
+
+
 def _mean_abs(F: torch.Tensor, rows: np.ndarray) -> np.ndarray:
     """mean |F| per (row, channel): the scale of the rounding error of the pooled sum."""
     out = []
@@ -205,7 +222,7 @@ def check_batch(ctx: Smtm, mem: O.Memory, w: Workload, fmaps: List[torch.Tensor]
         assert int(n_exit_dev.item()) == n_exit and int(n_live_dev.item()) == n_live_next
 
         # ---- oracle on the same bits, from the library's live set (teacher forcing)
-        F_host = F_in.cpu().numpy()
+        F_host = to_host(F_in)
         full = fused in (False, "lookup_exit")           # semantic vectors and top-2 values were captured
         with_sims = check_sims and fused is False
         ref = mem.stage(l, F_host, row_ids=rows_host.astype(np.int32) if mode != "dense" else None,

@@ -877,59 +877,70 @@ def test_stage_nhwc_is_encode_nhwc_plus_lookup_exit():
 
 # ------------------------------------------------------------------ workload 5 at its full length
 
-def test_adaptive_stream_full_length():
+class _Stream:
+    """State of the 100,000-frame run, carried from one part of the test to the next."""
+    PARTS = 4
+
+    def __init__(self):
+        self.w = configs.ADAPTIVE
+        self.cents = streams.centroids(self.w)
+        self.ls = streams.labels(self.w)
+        self.n_batches = (self.w.total_frames + self.w.batch - 1) // self.w.batch
+        self.ctx = P.make_ctx(self.w, self.cents, self.ls.initial_hot)
+        self.mem = P.make_oracle(self.w, self.cents, self.ls.initial_hot)
+        self.rep = P.ParityReport()
+        self.next_batch = 0
+        self.hot_sizes = []
+        self.exits_total = np.zeros(self.w.n_exits + 1, np.int64)
+        self.worst_centre = 0.0
+
+
+@pytest.fixture(scope="module")
+def adaptive_stream():
+    st = _Stream()
+    yield st
+    st.ctx.close()
+
+
+@pytest.mark.parametrize("part", range(_Stream.PARTS))
+def test_adaptive_stream_full_length(adaptive_stream, part):
     # 100,000 frames = 195 batches of 512 and one of 160, memory update after every batch, the most probable
-    # classes re-drawn every 10,000 frames.  Every batch runs through the library; every 12th batch (and the
-    # short last one) is also run through the oracle with full parity checks.  In between, the oracle's memory
-    # is set from the library's exported state (teacher forcing of the state), so each checked batch starts
-    # from identical memories and a slow drift cannot hide.
-    w = configs.ADAPTIVE
-    cents = streams.centroids(w)
-    ls = streams.labels(w)
-    n_batches = (w.total_frames + w.batch - 1) // w.batch
-    assert n_batches == 196 and w.total_frames - 195 * w.batch == 160
-    ctx = P.make_ctx(w, cents, ls.initial_hot)
-    mem = P.make_oracle(w, cents, ls.initial_hot)
-    rep = P.ParityReport()
-    i32 = dict(dtype=torch.int32, device=DEV)
-    hot_sizes, exits_total, worst_centre = [], np.zeros(w.n_exits + 1, np.int64), 0.0
-    for b in range(n_batches):
-        fm = streams.batch_feature_maps(w, cents, ls, b, DEV)
+    # classes re-drawn every 10,000 frames.  EVERY batch goes through the library and through the oracle:
+    # decisions, labels, lists and top-2 values at every exit point, then tables, order, size and centres after
+    # the memory update.  Nothing is ever copied from the library into the oracle except the live set and labels
+    # after a counted in-band flip (teacher forcing).  The run is cut into parts only to keep each test short.
+    st = adaptive_stream
+    w = st.w
+    assert st.n_batches == 196 and w.total_frames - 195 * w.batch == 160
+    per = (st.n_batches + _Stream.PARTS - 1) // _Stream.PARTS
+    lo, hi = part * per, min(st.n_batches, (part + 1) * per)
+    if st.next_batch != lo:
+        pytest.skip("the parts of the stream run in order; an earlier part did not run or failed")
+    for b in range(lo, hi):
+        fm = streams.batch_feature_maps(w, st.cents, st.ls, b, DEV)
         Bi = fm[0].shape[0]
-        truth = ls.label[b * w.batch: b * w.batch + Bi]
-        if b % 12 == 0 or b == n_batches - 1:
-            P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), check_sims=False, report=rep,
-                          fused="lookup_exit")
-            label = np.where(mem.exit_layer > 0, mem.label, truth).astype(np.int32)
-            _, e = P.check_cache_update(ctx, mem, label, mem.exit_layer.astype(np.int32))
-            worst_centre = max(worst_centre, e)
-            layer = mem.exit_layer
-        else:
-            ctx.begin_batch(Bi)
-            for l in range(1, w.n_exits + 1):
-                ctx.stage(l, fm[l - 1], row_ids=ctx.live_ids())
-            res = [torch.zeros(Bi, **i32) for _ in range(3)]
-            ctx.batch_results(*res)
-            layer = res[0].cpu().numpy()
-            label = np.where(layer > 0, res[1].cpu().numpy(), truth).astype(np.int32)
-            ctx.cache_update(torch.from_numpy(label).to(DEV), res[0], Bi)
-            # the oracle's memory follows the library's
-            ft, ts, hot, k = ctx.tables_export()
-            mem.FT[:] = ft; mem.TS[:] = ts; mem.hot_ids = hot.copy()
-            for l in range(1, w.n_exits + 1):
-                cg, mg = ctx.memory_export(l)
-                mem.SC[l - 1][:] = cg; mem.m[l - 1][:] = mg
-        exits_total += np.bincount(layer, minlength=w.n_exits + 1)
-        hot_sizes.append(len(mem.hot_ids))
+        truth = st.ls.label[b * w.batch: b * w.batch + Bi]
+        P.check_batch(st.ctx, st.mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), check_sims=False, report=st.rep,
+                      fused="lookup_exit")
+        label = np.where(st.mem.exit_layer > 0, st.mem.label, truth).astype(np.int32)
+        _, e = P.check_cache_update(st.ctx, st.mem, label, st.mem.exit_layer.astype(np.int32))
+        st.worst_centre = max(st.worst_centre, e)
+        st.exits_total += np.bincount(st.mem.exit_layer, minlength=w.n_exits + 1)
+        st.hot_sizes.append(len(st.mem.hot_ids))
+        st.next_batch = b + 1
         if b % 20 == 0:
-            _say(f"  batch {b}: hot size {hot_sizes[-1]}, exits so far {exits_total.tolist()}, flips {rep.in_band_flips}")
-    ctx.close()
-    _say("  hot sizes min/max", min(hot_sizes), max(hot_sizes), "exit histogram", exits_total.tolist(),
-         "checked frames", rep.frames, "flips", rep.in_band_flips, "worst centre error", worst_centre)
-    assert exits_total.sum() == w.total_frames
-    assert w.hot_min <= min(hot_sizes) and max(hot_sizes) <= w.hot_max and len(set(hot_sizes)) > 3
-    assert rep.in_band_flips <= rep.frames // 50
-    assert exits_total[0] < 0.2 * w.total_frames            # with the update running, most frames are released early
+            _say(f"  batch {b}: hot size {st.hot_sizes[-1]}, exits so far {st.exits_total.tolist()}, "
+                 f"flips {st.rep.in_band_flips}")
+    if hi == st.n_batches:
+        rep = st.rep
+        _say("  hot sizes min/max", min(st.hot_sizes), max(st.hot_sizes), "exit histogram", st.exits_total.tolist(),
+             "frames compared", rep.frames, "in-band frames", rep.in_band_frames, "flips", rep.in_band_flips,
+             "of them outside the narrow band", rep.flips_outside_narrow_band, "label-only differences",
+             rep.label_only_diffs, "worst centre error", st.worst_centre)
+        assert rep.frames == w.total_frames == st.exits_total.sum()
+        assert w.hot_min <= min(st.hot_sizes) and max(st.hot_sizes) <= w.hot_max and len(set(st.hot_sizes)) > 3
+        assert rep.in_band_flips <= rep.frames // 1000
+        assert st.exits_total[0] < 0.2 * w.total_frames      # with the update running, most frames are released early
 
 
 def test_cache_update_with_the_batchs_own_results():
