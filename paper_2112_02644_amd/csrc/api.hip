@@ -466,6 +466,8 @@ static int32_t check_compact_args(smtm_ctx* ctx, const int32_t* live_ids, const 
     return SMTM_OK;
 }
 
+constexpr int kFusedDecideRows = 2048;   // largest batch whose decisions are made inside the compaction kernel
+
 static CompactArgs compact_args(smtm_ctx* ctx, int32_t exit, int32_t* exit_ids, int32_t* exit_labels,
                                 int32_t* exit_tier, int32_t* n_exit_dev, int32_t* live_ids, int32_t* n_live_dev) {
     CompactArgs a;
@@ -561,8 +563,15 @@ int32_t smtm_lookup_exit(smtm_ctx* ctx, int32_t exit, float* top_val, int32_t* t
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     enqueue_score(ctx, exit, nullptr, st);
-    launch_decide_compact(decide_args(ctx, top_val, top_id),
-                          compact_args(ctx, exit, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids, n_live_dev), st);
+    // The fused kernel is one block: it merges a slot's per-tile results on one CU, which for a long batch takes
+    // longer than a launch (14 against 12 us at 4096 frames).  Long batches decide on many CUs first.
+    if (ctx->batch > kFusedDecideRows) {
+        launch_decide(decide_args(ctx, top_val, top_id), st);
+        launch_compact(compact_args(ctx, exit, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids, n_live_dev), st);
+    } else {
+        launch_decide_compact(decide_args(ctx, top_val, top_id),
+                              compact_args(ctx, exit, exit_ids, exit_labels, exit_tier, n_exit_dev, live_ids, n_live_dev), st);
+    }
     if (fmap_out)
         launch_gather_rows(fmap_in, row_ids, ctx->next_slots, ctx->counts, ctx->batch, fmap_out, row_bytes, st);
     rc = check_launch(ctx, "smtm_lookup_exit");

@@ -50,31 +50,29 @@ __device__ __forceinline__ void compact_block(const CompactArgs& a, const Decide
     // kernel before; fetched one after the other it would cost three round trips).  The lists have
     // max_rows entries.
     int n_live = a.counts->n_live;
-    int d0 = 0, frame0 = 0, lab0 = -1;
-    SlotTop2 m0 = {};
-    if (tid < a.max_rows) {
-        frame0 = a.frame_ids[tid];
-        if (!g) { d0 = a.decision[tid]; lab0 = a.label[tid]; }
-        else m0 = merge_slot(*g, tid);                   // loads only, valid for any slot of the batch
-    }
-    asm volatile("" : "+v"(d0), "+v"(frame0), "+v"(lab0), "+s"(n_live));   // issued before any is waited for
+    int d_nx = 0, frame_nx = 0, lab_nx = -1;             // what the next chunk's slot of this thread will need
+    SlotTop2 m_nx = {};
+    auto prefetch = [&](int slot) {                      // loads only; any slot of the batch is readable
+        if (slot < a.max_rows) {
+            frame_nx = a.frame_ids[slot];
+            if (!g) { d_nx = a.decision[slot]; lab_nx = a.label[slot]; }
+            else m_nx = merge_slot(*g, slot);
+        }
+    };
+    prefetch(tid);
+    asm volatile("" : "+v"(d_nx), "+v"(frame_nx), "+v"(lab_nx), "+s"(n_live));   // issued before any is waited for
     if (tid == 0) { base_exit = 0; base_t1 = 0; }
     __syncthreads();
     for (int c0 = 0; c0 < n_live; c0 += BS) {            // uniform over the block
         const int slot = c0 + tid;
         const bool valid = slot < n_live;
-        int d = 0, frame = 0, lab = -1;
+        int d = d_nx, lab = lab_nx;
+        const int frame = frame_nx;
+        const SlotTop2 m = m_nx;
+        if (c0 + BS < n_live) prefetch(slot + BS);       // the next chunk's loads fly during this chunk's scan
         if (valid) {
-            if (c0 == 0) { d = d0; frame = frame0; lab = lab0; }
-            else {
-                frame = a.frame_ids[slot];
-                if (!g) { d = a.decision[slot]; lab = a.label[slot]; }
-            }
-            if (g) {
-                const SlotDecision sd = c0 == 0 ? finish_slot(*g, slot, m0) : decide_slot(*g, slot);
-                d = sd.d; lab = sd.label;
-            }
-        }
+            if (g) { const SlotDecision sd = finish_slot(*g, slot, m); d = sd.d; lab = sd.label; }
+        } else { d = 0; lab = -1; }
         const bool ex = valid && d != 0;
         const unsigned long long m_ex = __ballot(ex);
         const unsigned long long m_t1 = __ballot(valid && d == 1);

@@ -271,8 +271,10 @@ __device__ __forceinline__ void multiply_stage(const StageRegs<NJ>& R, const flo
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The variant for few stages keeps its registers under 256 so that two blocks share a CU: with a short K loop a
+// block is little more than its chain of dependent memory round trips, and only other blocks can fill those.
 template <bool SPLITK>
-__global__ __launch_bounds__(256) void k_score_mfma(ScoreArgs a, const _Float16* __restrict__ chat, int Cp) {
+__global__ __launch_bounds__(256, SPLITK ? 1 : 2) void k_score_mfma(ScoreArgs a, const _Float16* __restrict__ chat, int Cp) {
     constexpr int NJ = SPLITK ? 4 : 1;
     constexpr int COPIES = SPLITK ? 4 : 1;
     __shared__ __attribute__((aligned(16))) float red[COPIES * SC_M * SC_LD];
@@ -359,7 +361,11 @@ __global__ __launch_bounds__(256) void k_score_mfma(ScoreArgs a, const _Float16*
 void launch_score_mfma(const ScoreArgs& a, const _Float16* chat, int Cp, hipStream_t st) {
     // centres are padded to kRowPad = 128 classes and Cp is a multiple of 64: a tile never reads outside them
     dim3 grid((a.n + SC_N - 1) / SC_N, (a.max_rows + SC_M - 1) / SC_M);
-    if (Cp / 64 >= 4) hipLaunchKernelGGL((k_score_mfma<true>), grid, dim3(256), 0, st, a, chat, Cp);
+    // Splitting K over the wavefronts shortens a block's chain of stages but costs the registers that would let
+    // two blocks share a CU: worth it for long K, or when there are too few blocks to fill the CUs twice anyway.
+    const int n_stage = Cp / 64;
+    const bool split = n_stage >= 4 && (n_stage >= 16 || (int64_t)grid.x * grid.y <= 512);
+    if (split) hipLaunchKernelGGL((k_score_mfma<true>), grid, dim3(256), 0, st, a, chat, Cp);
     else hipLaunchKernelGGL((k_score_mfma<false>), grid, dim3(256), 0, st, a, chat, Cp);
 }
 
