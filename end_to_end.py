@@ -12,7 +12,9 @@ Images: a class is a texture (a mean colour plus a few coloured gratings of its 
 orientations), a frame is its class texture at fresh phases plus per-pixel Gaussian noise;
 off-memory frames show a texture of their own.  Centres come from the library's warm-up over a labelled pass of the same generator.
 
-    python -m paper_2112_02644_amd.end_to_end --batch 1024 --taus 0.02 0.01 0.005
+    python end_to_end.py --batch 1024 --taus 0.02 0.01 0.005
+
+A demonstration next to the benchmark, not part of the library: the convolutions are PyTorch's.
 """
 from __future__ import annotations
 
@@ -25,6 +27,10 @@ import time
 from typing import Dict, List, Sequence
 
 import numpy as np
+
+ROOT = __import__("pathlib").Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
 
 STAGES = ((64, 256, 3, 1), (128, 512, 4, 2), (256, 1024, 6, 2), (512, 2048, 3, 2))   # mid, out, blocks, stride
 SEED = 20211202
@@ -229,7 +235,7 @@ def run(batch: int, taus: Sequence[float], n_classes: int, hot: int, reps: int, 
         bucket: int, device: str = "cuda:0") -> Dict:
     import torch
     from workloads import configs, streams
-    from .smtm import Smtm, SmtmConfig
+    from paper_2112_02644_amd import Smtm, SmtmConfig
 
     torch.backends.cudnn.benchmark = False
     w = dataclasses.replace(configs.RESNET50, n_classes=n_classes, hot=hot, batch=batch)

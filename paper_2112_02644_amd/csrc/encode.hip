@@ -529,6 +529,76 @@ __global__ __launch_bounds__(1024) void k_encode_nhwc(
     }
 }
 
+// Channels-last maps with few positions (7x7, 14x14) and wide rows: a wavefront takes a (frame, slab of 64
+// chunks) alone and walks the positions, 1 KB per load, UNR loads in flight, a lane adding up its own 16-byte chunk
+// of channels in registers.  No LDS and no barrier; the slab is one bin of the frame's partial maxima.
+template <typename T, int UNR>
+__global__ __launch_bounds__(256) void k_encode_nhwc_wave(
+    const T* __restrict__ F, const int32_t* __restrict__ row_ids,
+    const int32_t* __restrict__ frame_ids, const Counts* __restrict__ counts, int max_rows,
+    EncodeOut o, int C, int HW) {
+    constexpr int E = 16 / (int)sizeof(T);               // channels per 16-byte chunk
+    const int lane = threadIdx.x & 63;
+    const int cpr = C / E;                               // chunks per position row, a multiple of 64 here
+    const int n_slabs = cpr >> 6;                        // tasks per frame = bins per frame
+    const int n_live = live_count(o, counts, max_rows);
+    const int64_t total = (int64_t)n_live * n_slabs;
+    const int64_t n_waves = (int64_t)gridDim.x * 4;
+    for (int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); t < total; t += n_waves) {
+        const int slot = (int)(t / n_slabs);
+        const int slab = (int)(t - (int64_t)slot * n_slabs);
+        const int frame = o.fresh ? slot : frame_ids[slot];
+        const int64_t row = row_ids ? row_ids[slot] : slot;
+        const u32x4* base = reinterpret_cast<const u32x4*>(F + row * (int64_t)HW * C) + slab * 64 + lane;
+        float acc[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] = 0.f;
+        for (int p0 = 0; p0 < HW; p0 += UNR) {
+            u32x4 v[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+                v[u] = p0 + u < HW ? __builtin_nontemporal_load(base + (int64_t)(p0 + u) * cpr) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                if (sizeof(T) == 2) {
+                    const uint32_t w4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const half2_t h = __builtin_bit_cast(half2_t, w4[q]);
+                        acc[(2 * q) % E] += (float)h.x;
+                        acc[(2 * q + 1) % E] += (float)h.y;
+                    }
+                } else {
+                    const f32x4 f = __builtin_bit_cast(f32x4, v[u]);
+                    acc[0] += f.x; acc[1 % E] += f.y; acc[2 % E] += f.z; acc[3 % E] += f.w;
+                }
+            }
+        }
+        uint32_t mx = 0u;
+        const int c0 = (slab * 64 + lane) * E;
+        float m[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            m[e] = acc[e] / (float)HW;
+            const uint32_t b = abs_bits(m[e]);
+            mx = b > mx ? b : mx;
+        }
+        float* dst = o.sv + (int64_t)slot * o.ldv + c0;               // 16-byte aligned: ldv and c0 are multiples of 4
+#pragma unroll
+        for (int e = 0; e < E; e += 4) *reinterpret_cast<f32x4*>(dst + e) = f32x4{m[e], m[e + 1], m[e + 2], m[e + 3]};
+        if (o.sv_out) {
+            float* q = o.sv_out + (int64_t)slot * C + c0;
+#pragma unroll
+            for (int e = 0; e < E; ++e) q[e] = m[e];
+        }
+        mx = wave_max_u32(mx);
+        if (lane == 0) {
+            o.rowmax[(int64_t)slot * kRowMaxSlots + slab] = mx;
+            if (slab == 0) o.slot_of[frame] = slot;
+        }
+    }
+}
+
 // Fallback for channel counts that are not a multiple of a 16-byte chunk: lane = channel,
 // positions walked one by one (coalesced over channels).
 template <typename T>
@@ -710,6 +780,20 @@ const char* launch_encode_nhwc(const void* fmap, int dtype, int C, int HW, const
     if (C % E == 0) {
         const int cpr = C / E;
         const int n_slabs = (cpr + 63) / 64;
+        if (cpr % 64 == 0 && n_slabs <= kRowMaxSlots && HW <= 256 && (int64_t)max_rows * n_slabs >= 2048) {
+            // few positions, full slabs, enough (frame, slab) pairs to give every SIMD several wavefronts
+            *slots = n_slabs;
+            const int grid = encode_grid((int64_t)max_rows * n_slabs, 4);
+            // loads in flight per lane: 49 positions in two rounds of 25, more positions in rounds of 16
+#define SMTM_LAUNCH_NHWC_WAVE(T, UNR)                                                                       \
+            hipLaunchKernelGGL((k_encode_nhwc_wave<T, UNR>), dim3(grid), dim3(256), 0, st,                  \
+                               static_cast<const T*>(fmap), row_ids, frame_ids, counts, max_rows, out, C, HW)
+            if (dtype == SMTM_F16) { if (HW <= 50) SMTM_LAUNCH_NHWC_WAVE(_Float16, 25); else SMTM_LAUNCH_NHWC_WAVE(_Float16, 16); }
+            else                   { if (HW <= 50) SMTM_LAUNCH_NHWC_WAVE(float, 25);    else SMTM_LAUNCH_NHWC_WAVE(float, 16); }
+#undef SMTM_LAUNCH_NHWC_WAVE
+            if (name) snprintf(name, name_cap, "k_encode_nhwc_wave<%s>", dtype == SMTM_F16 ? "f16" : "f32");
+            return "nhwcw";
+        }
         const int sw = cpr < 64 ? cpr : 64, ppl = 64 / sw;
         // wavefronts per block: enough that each still issues several loads, at most 16
         int nw = HW / (ppl * 8);

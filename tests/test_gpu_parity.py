@@ -811,6 +811,39 @@ def test_encode_nhwc_shapes(dtype, rows, C, H, W, use_ids):
     ctx.close()
 
 
+@pytest.mark.parametrize("C,H,W", [(256, 56, 56), (512, 28, 28), (1024, 14, 14), (2048, 7, 7)])
+def test_encode_nhwc_full_batch(C, H, W):
+    # channels-last encode at the real batch of the ResNet-50-shaped workload, every element against the oracle
+    _say("encode nhwc full batch", C, H, W)
+    B = 1024
+    g = torch.Generator(device=DEV).manual_seed(C + H)
+    F = (torch.randn(B, H, W, C, device=DEV, generator=g) * 0.6 + 0.05).to(torch.float16)
+    ctx = Smtm(SmtmConfig(n_classes=4, dims=[C], max_batch=B, hot_init=2))
+    for use_ids in (False, True):
+        batch = B if not use_ids else 700
+        ctx.begin_batch(batch)
+        sv = torch.full((B, C), float("nan"), device=DEV)
+        perm, ids = None, None
+        if use_ids:
+            perm = np.sort(np.random.default_rng(C).permutation(B)[:batch]).astype(np.int32)
+            ids = torch.from_numpy(perm).to(DEV)
+        ctx.encode_nhwc(1, F, row_ids=ids, sv_out=sv)
+        torch.cuda.synchronize()
+        got = sv[:batch].cpu().numpy().astype(np.float64)
+        assert torch.isnan(sv[batch:]).all()
+        rows = np.arange(batch) if perm is None else perm
+        worst = 0.0
+        for lo in range(0, batch, 128):                   # the oracle reads NCHW: permute a slice at a time
+            sel = torch.from_numpy(rows[lo:lo + 128].astype(np.int64)).to(DEV)
+            Fn = F[sel].permute(0, 3, 1, 2).contiguous()
+            ref = O.encode(P.to_host(Fn))
+            scale = np.maximum(np.abs(ref), Fn.float().abs().mean(dim=(2, 3)).cpu().numpy())
+            worst = max(worst, float((np.abs(got[lo:lo + 128] - ref) / scale).max()))
+        _say("   kernel", ctx.encode_kernel(1), "worst error", worst)
+        assert worst <= P.SV_RTOL
+    ctx.close()
+
+
 def test_resnet50_channels_last_batch_matches_oracle_decisions():
     # the whole path on channels-last tensors: encode_nhwc + lookup_exit with the gather
     w = dataclasses.replace(configs.RESNET50, batch=256)
