@@ -205,14 +205,14 @@ def main() -> int:
             c2.hot_set(ls.initial_hot)
             st = torch.cuda.Stream()
             c2.stream = st.cuda_stream
-            return dict(ctx=c2, st=st, fmaps=[f.clone() for f in fmaps], gathers=[torch.empty_like(f) for f in fmaps],
+            return dict(ctx=c2, st=st, gathers=[torch.empty_like(f) for f in fmaps],
                         lists=[[torch.zeros(B, **i32) for _ in range(3)] for _ in range(L)])
 
-        def lane_step(lane):
+        def lane_step(lane, s):
             c2 = lane["ctx"]
             c2.begin_batch(B)
             for l in range(1, L + 1):
-                F = lane["fmaps"][l - 1]
+                F = stream_fmaps[s % n_distinct][l - 1]     # each lane walks the stream too, half a lap apart
                 ids = c2.live_ids()
                 c2.encode(l, F, row_ids=ids)
                 e = lane["lists"][l - 1]
@@ -226,8 +226,8 @@ def main() -> int:
             if k == args.warmup:
                 torch.cuda.synchronize()
                 t2 = time.perf_counter()
-            for lane in lanes:
-                lane_step(lane)
+            for i, lane in enumerate(lanes):
+                lane_step(lane, k + i * (n_distinct // 2))
         torch.cuda.synchronize()
         two_fps = 2 * B * args.steps / (time.perf_counter() - t2)
         for lane in lanes:
@@ -337,8 +337,8 @@ def main() -> int:
                     "ms": noexit_ms, "frames/s": B / (noexit_ms * 1e-3),
                     "GB/s": noexit_bytes / (noexit_ms * 1e-3) / 1e9,
                     "hbm_frac": noexit_bytes / (noexit_ms * 1e-3) / 1e9 / HBM_PEAK_GBS} if noexit_clean else None,
-        "two_contexts": {"what": "two independent frame streams (two contexts, own memory and tensors) on two HIP "
-                                 "streams, same step each; aggregate", "frames/s": two_fps} if two_fps else None,
+        "two_contexts": {"what": "two independent frame streams (two contexts with their own memory, walking the same "
+                                 "stream of batches half a lap apart) on two HIP streams; aggregate", "frames/s": two_fps} if two_fps else None,
         "one_frame": {"what": "batch of one through every exit point and the memory update, replayed from a HIP "
                               "graph; microseconds per frame", "us": one_frame_us} if one_frame_us else None,
         # survivors after each exit point for every step run (warm-up included), so that per-dispatch
