@@ -345,14 +345,19 @@ def check_batch(ctx: Smtm, mem: O.Memory, w: Workload, fmaps: List[torch.Tensor]
 
 
 def check_cache_update(ctx: Smtm, mem: O.Memory, label: np.ndarray, stop_layer: np.ndarray,
-                       centre_rtol: float = 1e-5):
+                       centre_rtol: float = 1e-5, own: bool = False):
     """Memory update on both sides from the same labels; tables / order / size bit-exact,
-    centres within centre_rtol of the oracle's (relative to the centre's largest component)."""
+    centres within centre_rtol of the oracle's (relative to the centre's largest component).
+    own: the library takes labels and stop layers from its own per-frame results of the batch (the
+    arrays given here are then what the oracle's side of the batch says those results are)."""
     dev = "cuda"
     B = len(label)
-    lab_d = torch.from_numpy(label.astype(np.int32)).to(dev)
-    stop_d = torch.from_numpy(stop_layer.astype(np.int32)).to(dev)
-    ctx.cache_update(lab_d, stop_d, B)
+    if own:
+        ctx.cache_update(None, None, B)
+    else:
+        lab_d = torch.from_numpy(label.astype(np.int32)).to(dev)
+        stop_d = torch.from_numpy(stop_layer.astype(np.int32)).to(dev)
+        ctx.cache_update(lab_d, stop_d, B)
     torch.cuda.synchronize()
     upd = mem.cache_update(label, stop_layer)
     ft, ts, hot, k = ctx.tables_export()

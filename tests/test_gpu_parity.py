@@ -223,6 +223,29 @@ def test_resnet50_lookup_exit_full_size():
     assert sum(rep.exit_hist) == w.batch and rep.in_band_flips <= w.batch // 50
 
 
+def test_resnet50_stream_as_the_benchmark_walks_it():
+    # three consecutive batches of the stream in the benchmark's launch configuration: full-batch tensors read
+    # through the live list, encode + lookup_exit with the survivors gathered, and the memory updated after
+    # every batch from the batch's own results (frames that ran to the end carry no label)
+    w = configs.RESNET50
+    cents = streams.centroids(w)
+    ls = streams.labels(w, w.batch * 3)
+    ctx = P.make_ctx(w, cents, ls.initial_hot)
+    mem = P.make_oracle(w, cents, ls.initial_hot)
+    rep = P.ParityReport()
+    for b in range(3):
+        fm = streams.batch_feature_maps(w, cents, ls, b, DEV)
+        P.check_batch(ctx, mem, w, fm, tau=w.tau, rtol=P.sim_rtol(w), check_sims=False, report=rep,
+                      fused="lookup_exit", mode="row_ids")
+        label = np.where(mem.exit_layer > 0, mem.label, -1).astype(np.int32)
+        _, e = P.check_cache_update(ctx, mem, label, mem.exit_layer.astype(np.int32), own=True)
+        _say(f"  batch {b}: exits so far {rep.exit_hist} flips {rep.in_band_flips} (outside the narrow band "
+             f"{rep.flips_outside_narrow_band}) centre err {e:.2e}")
+        del fm
+    assert rep.frames == 3 * w.batch and rep.in_band_flips <= rep.frames // 50
+    ctx.close()
+
+
 def test_mobilenetv2_full_size():
     w = configs.MOBILENETV2
     _say("mobilenetv2 full size")
