@@ -53,7 +53,8 @@ extern "C" {
 /* how the similarities of Eq. 1 are computed */
 #define SMTM_SCORE_AUTO   0   /* fp16 feature maps -> MFMA, fp32 feature maps -> FP32 */
 #define SMTM_SCORE_FP32   1   /* fp32 operands, fp32 vector arithmetic */
-#define SMTM_SCORE_MFMA   2   /* unit-normalised fp16 operands on the matrix cores, fp32 accumulate */
+#define SMTM_SCORE_MFMA   2   /* fp16 operands on the matrix cores (unit centres; semantic vectors scaled by a
+                                 power of two, their length taken in fp32), fp32 accumulate */
 
 /* how the forgetting of Sec. 6.1 acts on the frequency table */
 #define SMTM_FORGET_AT_SCORING 0   /* Eq. 5: Score = FT * 0.25^floor(TS/W), FT itself keeps the whole history */
