@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
 # profiles/encode_kernels_hbm_traffic.txt (same command, same workload).  Reported only while the kernel's
 # source is the one the counters were taken on; otherwise the field is null.
-TRAFFIC = {"workload": "resnet50", "bytes_per_launch": 1645585989.6,
+TRAFFIC = {"workload": "resnet50", "bytes_per_launch": 1645583082.8,
            "encode_sha256": "9fa795b93429140b7650dc784deb98f67b2fbf7c4079b6273e1593f2215e59b9"}
 
 
